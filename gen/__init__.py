@@ -148,7 +148,7 @@ def draft_tokens(g: np.random.Generator, parent: np.ndarray, V: int) -> np.ndarr
         s = used.setdefault(p, set())
         while True:
             t = int(g.integers(0, V))
-            if t not in s:
+            if t not in s or len(s) >= V:     # a vocabulary smaller than the fan-out must repeat
                 break
         s.add(t)
         tok[i] = t

@@ -1,0 +1,196 @@
+/*
+ * libvispec_verify — tree verification for speculative decoding on MI355X (gfx950).
+ *
+ * The target model of a speculative decoder scores a whole draft token tree in one
+ * forward pass and keeps the longest accepted root-to-node path (paper Section 3.1;
+ * image embeddings are ordinary context positions, Section 3.2, so the KV cache the
+ * tree attends to is dominated by thousands of image tokens). This library is that
+ * step's data-parallel part:
+ *
+ *   vs_tree_mask_build        ancestor-or-self bit masks and depths of a draft tree
+ *   vs_tree_verify_attention  softmax attention (paper Eq. 1, with the usual scale)
+ *                             of the T tree queries over prefix + visible tree keys
+ *   vs_tree_accept            vocab-wide argmax per node, longest accepted path and
+ *                             bonus token (Section 3.1 at temperature 0)
+ *
+ * Conventions
+ *   - C ABI, no exceptions cross it. Every function returns an int32 vs_error
+ *     (0 = VS_OK, negative = error found on the host before anything was enqueued).
+ *   - Unless a parameter says "host", every data pointer is a DEVICE pointer owned by
+ *     the caller; the library neither allocates nor frees device memory. Scratch
+ *     comes from a caller-supplied workspace sized by the matching *_workspace_bytes.
+ *   - Calls enqueue kernels on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and return without synchronising. Outputs are valid once the
+ *     stream has been synchronised. Calls that share a workspace must be ordered on
+ *     one stream.
+ *   - Data-dependent problems (a malformed tree, a prefix length outside the cache, a
+ *     block id outside the pool) cannot be seen by the host. The kernels report them
+ *     per sequence in the optional device array `status` (vs_status, 0 = ok), never
+ *     read out of bounds, and leave that sequence's outputs unspecified.
+ *   - A tree has T nodes, 1 <= T <= 64. Node 0 is the root: the last committed token,
+ *     whose K/V are not yet part of the prefix. parent[0] = -1 and 0 <= parent[i] < i.
+ */
+#ifndef VISPEC_VERIFY_H
+#define VISPEC_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VS_VERSION 100 /* major*10000 + minor*100 + patch */
+#define VS_MAX_TREE 64
+
+typedef enum vs_error {
+    VS_OK = 0,
+    VS_ERR_NULL = -1,      /* a required pointer is NULL */
+    VS_ERR_SHAPE = -2,     /* B < 1, T outside [1,64], Hq % Hkv != 0, unsupported head_dim, V < 1 ... */
+    VS_ERR_DTYPE = -3,     /* dtype is neither VS_BF16 nor VS_F32 */
+    VS_ERR_WORKSPACE = -4, /* workspace NULL or smaller than *_workspace_bytes reports */
+    VS_ERR_HIP = -5,       /* the HIP runtime refused a launch */
+    VS_ERR_LAYOUT = -6,    /* strides / alignment / paging parameters not supported */
+    VS_ERR_NO_DEVICE = -7  /* no usable gfx950 device */
+} vs_error;
+
+/* Per-sequence result codes written by the kernels into `status`. */
+typedef enum vs_status {
+    VS_STATUS_OK = 0,
+    VS_STATUS_BAD_ROOT = 1,   /* parent[0] != -1 */
+    VS_STATUS_BAD_PARENT = 2, /* some parent[i], i >= 1, outside [0, i) */
+    VS_STATUS_BAD_PREFIX = 3, /* prefix_len < 0, > max_prefix_len, or prefix_len + T beyond the cache */
+    VS_STATUS_BAD_BLOCK = 4   /* a block-table entry in use lies outside [0, num_blocks) */
+} vs_status;
+
+typedef enum vs_dtype { VS_BF16 = 0, VS_F32 = 1 } vs_dtype;
+
+/* Which attention kernel to run. AUTO picks MFMA for bf16 and GENERIC for fp32. */
+typedef enum vs_attn_impl { VS_IMPL_AUTO = 0, VS_IMPL_GENERIC = 1, VS_IMPL_MFMA = 2 } vs_attn_impl;
+
+int32_t vs_version(void);
+const char* vs_strerror(int32_t err);       /* static string for a vs_error */
+const char* vs_status_string(int32_t code); /* static string for a vs_status */
+
+/* Host twin of the kernels' tree check: `parent` is a HOST array of T entries.
+ * Returns the vs_status the kernels would report for this tree (VS_STATUS_OK,
+ * VS_STATUS_BAD_ROOT, VS_STATUS_BAD_PARENT), or VS_ERR_NULL / VS_ERR_SHAPE. */
+int32_t vs_tree_validate_host(const int32_t* parent, int32_t T);
+
+/*
+ * Ancestor masks of B draft trees (Section 3.1: the draft tree proposes several
+ * candidate tokens per position; a node may attend to itself and its ancestors only).
+ *   parent  [B,T] int32   in   parent[b][0] = -1, 0 <= parent[b][i] < i
+ *   mask    [B,T] uint64  out  bit j of mask[b][i] set iff j == i or j is an ancestor of i
+ *   depth   [B,T] int32   out  edges from the root (root = 0)
+ *   status  [B]   int32   out, optional (may be NULL)
+ * An invalid tree gets its status set and its mask/depth rows zero-filled.
+ */
+int32_t vs_tree_mask_build(const int32_t* parent, int32_t B, int32_t T, uint64_t* mask,
+                           int32_t* depth, int32_t* status, void* stream);
+
+/*
+ * Attention problem description (host struct, read during the call only).
+ *
+ * Query head h reads KV head h / (Hq / Hkv). Each sequence's cache holds its
+ * prefix_len[b] context tokens (image and text alike) followed by the T tree nodes'
+ * own K/V at logical token slots prefix_len[b] .. prefix_len[b]+T-1, written by the
+ * caller before the call (the pre-allocated cache of the paper's Appendix A used the
+ * way a verify forward uses it). Whatever lies beyond slot prefix_len+T-1 is never
+ * read into the result. All K/V values in slots that are read must be finite.
+ *
+ * Element offset of (sequence b, KV head kv, logical token t, channel c):
+ *   contiguous (paged = 0):  b*stride_seq + kv*stride_head + t*stride_tok + c
+ *   paged      (paged = 1):  blk*stride_block + kv*stride_head + (t % block_size)*stride_tok + c
+ *                            with blk = block_table[b*max_blocks + t / block_size]
+ * The same layout applies to k_cache and v_cache. Channels are contiguous.
+ */
+typedef struct vs_attn_desc {
+    int32_t B;              /* sequences, >= 1 */
+    int32_t T;              /* tree nodes per sequence incl. root, 1..64 */
+    int32_t Hq;             /* query heads */
+    int32_t Hkv;            /* KV heads, divides Hq */
+    int32_t d;              /* head_dim: 64 or 128 */
+    int32_t dtype;          /* vs_dtype of q, k_cache, v_cache and out */
+    float softmax_scale;    /* > 0, multiplies q.k before softmax (Eq. 1 omits it) */
+    int32_t max_prefix_len; /* host-side upper bound on every prefix_len[b]; sizes the launch */
+    int32_t paged;          /* 0 contiguous, 1 paged */
+    int32_t block_size;     /* paged: tokens per block, power of two >= 16 */
+    int32_t max_blocks;     /* paged: row length of block_table */
+    int32_t num_blocks;     /* paged: blocks in the pool (for the bounds check) */
+    int64_t capacity;       /* contiguous: token slots per sequence (for the bounds check) */
+    int64_t stride_seq;     /* contiguous */
+    int64_t stride_block;   /* paged */
+    int64_t stride_head;
+    int64_t stride_tok;
+    const int32_t* block_table; /* paged: device [B, max_blocks] */
+    int32_t impl;           /* vs_attn_impl */
+    int32_t num_splits;     /* key splits per (sequence, KV head); 0 = choose */
+} vs_attn_desc;
+
+/* What a call with this descriptor would launch (for tests and reports). */
+typedef struct vs_attn_plan {
+    int32_t impl;            /* VS_IMPL_GENERIC or VS_IMPL_MFMA */
+    int32_t num_splits;      /* upper bound on key splits per (sequence, KV head) */
+    int32_t keys_per_split;
+    int32_t row_groups;      /* workgroups that share one (sequence, KV head, split) */
+    int32_t waves_per_group;
+    int32_t workgroups;      /* main kernel grid size */
+    int32_t combine;         /* 1 if a split-combine kernel follows */
+} vs_attn_plan;
+
+int32_t vs_attention_plan(const vs_attn_desc* desc, vs_attn_plan* plan); /* both host */
+size_t vs_attention_workspace_bytes(const vs_attn_desc* desc);           /* 0 on invalid desc */
+
+/*
+ * Tree-masked attention (Eq. 1 restricted by tree ancestry; Sections 3.1-3.2).
+ * For node i of sequence b and query head h the visible keys are all prefix tokens
+ * plus the tree slots of i's ancestor-or-self set; the result is
+ *   out[b,i,h,:] = sum_j softmax_j(softmax_scale * q[b,i,h,:].K[j,:]) V[j,:]
+ * with fp32 accumulation, rounded to the storage dtype (nearest even).
+ *   q           [B,T,Hq,d]  in, dense
+ *   k_cache, v_cache        in, layout per desc
+ *   prefix_len  [B] int32   in
+ *   tree_parent [B,T] int32 in
+ *   tree_mask   [B,T] uint64 in, optional: vs_tree_mask_build's output for the same
+ *               trees; NULL = derive the masks from tree_parent inside the kernel
+ *   out         [B,T,Hq,d]  out, dense
+ *   status      [B] int32   out, optional
+ *   workspace   device scratch of at least vs_attention_workspace_bytes(desc) bytes
+ *               (may be NULL when that is 0), 256-byte aligned
+ * bf16 MFMA path needs 16-byte aligned q/k/v/out and strides that are multiples of 8.
+ */
+int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const void* k_cache,
+                                 const void* v_cache, const int32_t* prefix_len,
+                                 const int32_t* tree_parent, const uint64_t* tree_mask, void* out,
+                                 int32_t* status, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
+size_t vs_accept_workspace_bytes(int32_t B, int32_t T, int32_t V);
+
+/*
+ * Greedy acceptance (Section 3.1 at temperature 0: a draft token is kept iff it is the
+ * target's argmax at its parent; the token after the last kept node is that node's own
+ * argmax. The acceptance length counts draft tokens only, Section 5.1 "Metrics").
+ *   logits       [B,T,ld_logits] fp32 in; row (b,i) = target logits at node i; ld_logits >= V
+ *   draft_tokens [B,T] int32 in; entry 0 (the root's committed token) is ignored
+ *   parent       [B,T] int32 in
+ *   accepted_len [B] int32 out; depth of the deepest accepted node (ties: lowest index)
+ *   path         [B,T] int32 out; path[b][0..accepted_len[b]] = root .. that node, rest -1
+ *   bonus_token  [B] int32 out; argmax at the last node of the path
+ *   row_argmax   [B,T] int32 out, optional; first index of each row's maximum
+ *                (strict '>' scan: ties and signed zeros keep the lowest index, NaN never
+ *                displaces a value, a NaN in column 0 is never displaced)
+ *   status       [B] int32 out, optional
+ *   workspace    at least vs_accept_workspace_bytes(B,T,V) bytes, 256-byte aligned
+ */
+int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V,
+                       const int32_t* draft_tokens, const int32_t* parent, int32_t B, int32_t T,
+                       int32_t* accepted_len, int32_t* path, int32_t* bonus_token,
+                       int32_t* row_argmax, int32_t* status, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VISPEC_VERIFY_H */

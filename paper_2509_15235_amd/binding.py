@@ -1,0 +1,145 @@
+"""ctypes binding: same names and argument order as include/vispec_verify.h."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libvispec_verify.so")
+
+VS_BF16, VS_F32 = 0, 1
+VS_IMPL_AUTO, VS_IMPL_GENERIC, VS_IMPL_MFMA = 0, 1, 2
+
+EXPORTED_SYMBOLS = [
+    "vs_version", "vs_strerror", "vs_status_string", "vs_tree_validate_host", "vs_tree_mask_build",
+    "vs_attention_plan", "vs_attention_workspace_bytes", "vs_tree_verify_attention",
+    "vs_accept_workspace_bytes", "vs_tree_accept",
+]
+
+
+class VSError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: vs_error {code} ({vs_strerror(code)})")
+        self.code = code
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("d", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+        ("max_prefix_len", ctypes.c_int32), ("paged", ctypes.c_int32), ("block_size", ctypes.c_int32),
+        ("max_blocks", ctypes.c_int32), ("num_blocks", ctypes.c_int32), ("capacity", ctypes.c_int64),
+        ("stride_seq", ctypes.c_int64), ("stride_block", ctypes.c_int64), ("stride_head", ctypes.c_int64),
+        ("stride_tok", ctypes.c_int64), ("block_table", ctypes.c_void_p), ("impl", ctypes.c_int32),
+        ("num_splits", ctypes.c_int32),
+    ]
+
+
+class AttnPlan(ctypes.Structure):
+    _fields_ = [
+        ("impl", ctypes.c_int32), ("num_splits", ctypes.c_int32), ("keys_per_split", ctypes.c_int32),
+        ("row_groups", ctypes.c_int32), ("waves_per_group", ctypes.c_int32), ("workgroups", ctypes.c_int32),
+        ("combine", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2509_15235_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        L.vs_version.restype = i32
+        L.vs_strerror.argtypes = [i32]
+        L.vs_strerror.restype = ctypes.c_char_p
+        L.vs_status_string.argtypes = [i32]
+        L.vs_status_string.restype = ctypes.c_char_p
+        L.vs_tree_validate_host.argtypes = [vp, i32]
+        L.vs_tree_validate_host.restype = i32
+        L.vs_tree_mask_build.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.vs_tree_mask_build.restype = i32
+        L.vs_attention_plan.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(AttnPlan)]
+        L.vs_attention_plan.restype = i32
+        L.vs_attention_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
+        L.vs_attention_workspace_bytes.restype = sz
+        L.vs_tree_verify_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_tree_verify_attention.restype = i32
+        L.vs_accept_workspace_bytes.argtypes = [i32, i32, i32]
+        L.vs_accept_workspace_bytes.restype = sz
+        L.vs_tree_accept.argtypes = [vp, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_tree_accept.restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(x):
+    """Device (or host) address of x: None, an int, a ctypes pointer, or anything with data_ptr()."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "ctypes"):
+        return x.ctypes.data
+    return ctypes.cast(x, ctypes.c_void_p).value
+
+
+def vs_version() -> int:
+    return lib().vs_version()
+
+
+def vs_strerror(code: int) -> str:
+    return lib().vs_strerror(code).decode()
+
+
+def vs_status_string(code: int) -> str:
+    return lib().vs_status_string(code).decode()
+
+
+def vs_tree_validate_host(parent, T: int) -> int:
+    """parent: host int32 array (numpy) of T entries."""
+    return lib().vs_tree_validate_host(_ptr(parent), T)
+
+
+def vs_tree_mask_build(parent, B, T, mask, depth, status=None, stream=None) -> int:
+    return lib().vs_tree_mask_build(_ptr(parent), B, T, _ptr(mask), _ptr(depth), _ptr(status), _ptr(stream))
+
+
+def vs_attention_plan(desc: AttnDesc):
+    plan = AttnPlan()
+    rc = lib().vs_attention_plan(ctypes.byref(desc), ctypes.byref(plan))
+    return rc, plan
+
+
+def vs_attention_workspace_bytes(desc: AttnDesc) -> int:
+    return lib().vs_attention_workspace_bytes(ctypes.byref(desc))
+
+
+def vs_tree_verify_attention(desc: AttnDesc, q, k_cache, v_cache, prefix_len, tree_parent, tree_mask, out,
+                             status=None, workspace=None, workspace_bytes=0, stream=None) -> int:
+    return lib().vs_tree_verify_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                          _ptr(prefix_len), _ptr(tree_parent), _ptr(tree_mask), _ptr(out),
+                                          _ptr(status), _ptr(workspace), workspace_bytes, _ptr(stream))
+
+
+def vs_accept_workspace_bytes(B: int, T: int, V: int) -> int:
+    return lib().vs_accept_workspace_bytes(B, T, V)
+
+
+def vs_tree_accept(logits, ld_logits, V, draft_tokens, parent, B, T, accepted_len, path, bonus_token,
+                   row_argmax=None, status=None, workspace=None, workspace_bytes=0, stream=None) -> int:
+    return lib().vs_tree_accept(_ptr(logits), ld_logits, V, _ptr(draft_tokens), _ptr(parent), B, T,
+                                _ptr(accepted_len), _ptr(path), _ptr(bonus_token), _ptr(row_argmax),
+                                _ptr(status), _ptr(workspace), workspace_bytes, _ptr(stream))

@@ -1,0 +1,168 @@
+// Greedy acceptance over a draft tree (paper Section 3.1 at temperature 0): a draft token
+// survives iff it equals the target's argmax at its parent; the deepest surviving node
+// ends the accepted path and its own argmax is the bonus token.
+//
+// Two kernels: (1) a bandwidth-bound scan that reduces each logits row to per-chunk
+// (max, first index) pairs, (2) one workgroup per sequence that finishes the row argmax
+// and walks the tree.
+#include "vs_device.h"
+
+namespace vs {
+
+namespace {
+
+struct Best {
+    float v;
+    int32_t i;
+};
+
+// Candidate (v, i) replaces the incumbent iff it is larger, or equal with a lower index.
+// NaN candidates never win ('>' and '==' are false for NaN).
+__device__ __forceinline__ void take(Best& b, float v, int32_t i) {
+    if (v > b.v || (v == b.v && i < b.i)) {
+        b.v = v;
+        b.i = i;
+    }
+}
+
+__device__ __forceinline__ Best wave_best(Best b) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(b.v, o);
+        const int32_t oi = __shfl_xor(b.i, o);
+        take(b, ov, oi);
+    }
+    return b;
+}
+
+// grid = (chunks, B*T), block = 256. Writes one (value, index) pair per (row, chunk).
+__global__ __launch_bounds__(kArgmaxBlock) void argmax_partial_kernel(const AcceptParams p) {
+    __shared__ float sv[kArgmaxBlock / kWave];
+    __shared__ int32_t si[kArgmaxBlock / kWave];
+    const int chunk = blockIdx.x;
+    const int64_t row = blockIdx.y;
+    const float* __restrict__ lg = p.logits + row * p.ld;
+    const int begin = chunk * p.chunk_elems;
+    const int end = min(p.V, begin + p.chunk_elems);
+    Best best = {-INFINITY, INT32_MAX};
+    if (p.vec_ok) {
+        const int nvec = (end - begin) >> 2;
+        const f32x4* __restrict__ lv = (const f32x4*)(lg + begin);
+        int k = threadIdx.x;
+        // four independent 16-byte loads in flight per thread
+        for (; k + 3 * kArgmaxBlock < nvec; k += 4 * kArgmaxBlock) {
+            const f32x4 a0 = __builtin_nontemporal_load(lv + k);
+            const f32x4 a1 = __builtin_nontemporal_load(lv + k + kArgmaxBlock);
+            const f32x4 a2 = __builtin_nontemporal_load(lv + k + 2 * kArgmaxBlock);
+            const f32x4 a3 = __builtin_nontemporal_load(lv + k + 3 * kArgmaxBlock);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) take(best, a0[e], begin + 4 * k + e);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) take(best, a1[e], begin + 4 * (k + kArgmaxBlock) + e);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) take(best, a2[e], begin + 4 * (k + 2 * kArgmaxBlock) + e);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) take(best, a3[e], begin + 4 * (k + 3 * kArgmaxBlock) + e);
+        }
+        for (; k < nvec; k += kArgmaxBlock) {
+            const f32x4 a = __builtin_nontemporal_load(lv + k);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) take(best, a[e], begin + 4 * k + e);
+        }
+        for (int t = begin + 4 * nvec + threadIdx.x; t < end; t += kArgmaxBlock) take(best, lg[t], t);
+    } else {
+        for (int t = begin + threadIdx.x; t < end; t += kArgmaxBlock) take(best, lg[t], t);
+    }
+    best = wave_best(best);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        sv[wave] = best.v;
+        si[wave] = best.i;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kArgmaxBlock / kWave; ++w) take(best, sv[w], si[w]);
+        p.part_val[row * p.chunks + chunk] = best.v;
+        p.part_idx[row * p.chunks + chunk] = best.i;
+    }
+}
+
+// grid = B, block = 256. Finishes the argmax of the sequence's T rows, then wave 0 walks
+// the tree (one lane per node).
+__global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) {
+    __shared__ int32_t sp[VS_MAX_TREE];
+    __shared__ int32_t sflag;
+    __shared__ int32_t samax[VS_MAX_TREE];
+    __shared__ int32_t spath[VS_MAX_TREE];
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int T = p.T;
+    const int32_t tree_code = load_tree(p.parent + (int64_t)b * T, T, sp, &sflag);
+
+    for (int i = wave; i < T; i += 4) {
+        const int64_t row = (int64_t)b * T + i;
+        Best best = {-INFINITY, INT32_MAX};
+        for (int c = lane; c < p.chunks; c += kWave) take(best, p.part_val[row * p.chunks + c], p.part_idx[row * p.chunks + c]);
+        best = wave_best(best);
+        if (lane == 0) {
+            // what a left-to-right '>' scan returns: a NaN in column 0 is never displaced,
+            // and a row with nothing above -inf keeps index 0
+            const float first = p.logits[row * p.ld];
+            int32_t idx = best.i;
+            if (first != first || idx == INT32_MAX) idx = 0;
+            samax[i] = idx;
+            if (p.row_argmax) p.row_argmax[row] = idx;
+        }
+    }
+    if (tid < T) spath[tid] = -1;
+    __syncthreads();
+
+    int32_t best_node = 0, alen = 0;
+    if (wave == 0 && tree_code == VS_STATUS_OK) {
+        int32_t key = -1;
+        if (lane < T) {
+            bool ok = true;
+            int32_t dep = 0;
+            int j = lane;
+            while (j > 0) {
+                const int pj = sp[j];
+                ok = ok && (p.draft[(int64_t)b * T + j] == samax[pj]);
+                j = pj;
+                ++dep;
+            }
+            if (ok) key = dep * 64 + (63 - lane); // deepest first, then lowest index
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) key = max(key, __shfl_xor(key, o));
+        best_node = 63 - (key & 63); // the root is always accepted, so key >= 63
+        alen = key >> 6;
+        if (lane == 0) {
+            int j = best_node;
+            for (int k = alen; k >= 0 && j >= 0; --k) {
+                spath[k] = j;
+                j = sp[j];
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < T) p.path[(int64_t)b * T + tid] = spath[tid];
+    if (tid == 0) {
+        if (p.status) p.status[b] = tree_code;
+        const bool good = tree_code == VS_STATUS_OK;
+        p.accepted_len[b] = good ? alen : 0;
+        p.bonus[b] = good ? samax[best_node] : -1;
+    }
+}
+
+} // namespace
+
+hipError_t launch_accept(const AcceptParams& p, hipStream_t s) {
+    hipLaunchKernelGGL(argmax_partial_kernel, dim3(p.chunks, p.B * p.T), dim3(kArgmaxBlock), 0, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(accept_walk_kernel, dim3(p.B), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+} // namespace vs

@@ -1,0 +1,272 @@
+// C-ABI entry points of libvispec_verify: host-side argument checks, launch planning and
+// kernel enqueues. Nothing here allocates device memory or synchronises.
+#include <math.h>
+#include <string.h>
+
+#include "vs_internal.h"
+
+namespace {
+
+using namespace vs;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+struct Plan {
+    int32_t impl, rpw, waves, row_groups, rows, rows_pad, num_splits, keys_per_split, total_wgs;
+};
+
+// Shape / dtype / layout checks that need no device. Returns VS_OK or a vs_error.
+int32_t check_desc(const vs_attn_desc* d) {
+    if (!d) return VS_ERR_NULL;
+    if (d->B < 1 || d->T < 1 || d->T > VS_MAX_TREE || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0)
+        return VS_ERR_SHAPE;
+    if (d->d != 64 && d->d != 128) return VS_ERR_SHAPE;
+    if (d->max_prefix_len < 0) return VS_ERR_SHAPE;
+    if (!(d->softmax_scale > 0.f) || !isfinite(d->softmax_scale)) return VS_ERR_SHAPE;
+    if (d->dtype != VS_BF16 && d->dtype != VS_F32) return VS_ERR_DTYPE;
+    if (d->impl != VS_IMPL_AUTO && d->impl != VS_IMPL_GENERIC && d->impl != VS_IMPL_MFMA) return VS_ERR_SHAPE;
+    if (d->impl == VS_IMPL_MFMA && d->dtype != VS_BF16) return VS_ERR_DTYPE;
+    if (d->num_splits < 0) return VS_ERR_SHAPE;
+    if (d->stride_head < 0 || d->stride_tok < d->d) return VS_ERR_LAYOUT;
+    const int64_t need = (int64_t)d->max_prefix_len + d->T;
+    if (d->paged) {
+        if (!is_pow2(d->block_size) || d->block_size < 16) return VS_ERR_LAYOUT;
+        if (d->max_blocks < 1 || d->num_blocks < 1 || d->stride_block < 0) return VS_ERR_LAYOUT;
+        if (!d->block_table) return VS_ERR_NULL;
+        if (need > (int64_t)d->max_blocks * d->block_size) return VS_ERR_LAYOUT;
+    } else {
+        if (d->stride_seq < 0 || d->capacity < 1) return VS_ERR_LAYOUT;
+        if (need > d->capacity) return VS_ERR_LAYOUT;
+    }
+    const bool mfma = d->impl == VS_IMPL_MFMA || (d->impl == VS_IMPL_AUTO && d->dtype == VS_BF16);
+    if (mfma) {
+        // 16-byte vector loads of 8 bf16
+        if (d->stride_head % 8 || d->stride_tok % 8 || (d->paged ? d->stride_block % 8 : d->stride_seq % 8))
+            return VS_ERR_LAYOUT;
+    }
+    return VS_OK;
+}
+
+Plan make_plan(const vs_attn_desc* d) {
+    Plan pl{};
+    const int group = d->Hq / d->Hkv;
+    pl.rows = d->T * group;
+    pl.rows_pad = (pl.rows + kRowBlock - 1) / kRowBlock * kRowBlock;
+    pl.impl = d->impl == VS_IMPL_AUTO ? (d->dtype == VS_BF16 ? VS_IMPL_MFMA : VS_IMPL_GENERIC) : d->impl;
+    if (pl.impl == VS_IMPL_GENERIC) {
+        pl.rpw = 0;
+        pl.waves = 1;
+        pl.row_groups = 1;
+        pl.num_splits = 1;
+        pl.keys_per_split = 0;
+        pl.total_wgs = d->B * d->T * d->Hq;
+        return pl;
+    }
+    const int nrb = pl.rows_pad / kRowBlock;
+    pl.rpw = nrb >= 2 ? 2 : 1;
+    const int need = (nrb + pl.rpw - 1) / pl.rpw;
+    pl.waves = 1;
+    while (pl.waves < need && pl.waves < kMaxWaves) pl.waves *= 2;
+    pl.row_groups = (need + pl.waves - 1) / pl.waves;
+    const int tiles = ((int64_t)d->max_prefix_len + d->T + kTileKeys - 1) / kTileKeys;
+    const int units = d->B * d->Hkv * pl.row_groups;
+    int splits = d->num_splits;
+    if (splits <= 0) {
+        // enough workgroups to cover the 256 CUs (small workgroups: several per CU), but
+        // never fewer than two key tiles per split
+        const int target = 256 * (pl.waves >= 4 ? 1 : 4 / pl.waves);
+        splits = (target + units - 1) / units;
+        const int max_splits = (tiles + 1) / 2;
+        if (splits > max_splits) splits = max_splits;
+    }
+    if (splits < 1) splits = 1;
+    if (splits > tiles) splits = tiles;
+    const int tiles_per_split = (tiles + splits - 1) / splits;
+    pl.keys_per_split = tiles_per_split * kTileKeys;
+    pl.num_splits = (tiles + tiles_per_split - 1) / tiles_per_split;
+    pl.total_wgs = units * pl.num_splits;
+    return pl;
+}
+
+size_t workspace_bytes(const vs_attn_desc* d, const Plan& pl) {
+    if (pl.impl != VS_IMPL_MFMA || pl.num_splits <= 1) return 0;
+    const size_t prow = (size_t)d->B * d->Hkv * pl.num_splits * pl.rows_pad;
+    return align_up(prow * d->d * sizeof(float)) + align_up(prow * 2 * sizeof(float));
+}
+
+constexpr int kArgmaxChunk = 8192;
+
+int32_t accept_chunks(int32_t V) { return (V + kArgmaxChunk - 1) / kArgmaxChunk; }
+
+} // namespace
+
+extern "C" {
+
+int32_t vs_version(void) { return VS_VERSION; }
+
+const char* vs_strerror(int32_t err) {
+    switch (err) {
+    case VS_OK: return "ok";
+    case VS_ERR_NULL: return "a required pointer is NULL";
+    case VS_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case VS_ERR_DTYPE: return "unsupported dtype";
+    case VS_ERR_WORKSPACE: return "workspace missing or too small";
+    case VS_ERR_HIP: return "HIP runtime error at launch";
+    case VS_ERR_LAYOUT: return "unsupported strides, alignment or paging parameters";
+    case VS_ERR_NO_DEVICE: return "no usable gfx950 device";
+    default: return "unknown error";
+    }
+}
+
+const char* vs_status_string(int32_t code) {
+    switch (code) {
+    case VS_STATUS_OK: return "ok";
+    case VS_STATUS_BAD_ROOT: return "parent[0] is not -1";
+    case VS_STATUS_BAD_PARENT: return "a parent index is outside [0, i)";
+    case VS_STATUS_BAD_PREFIX: return "prefix_len outside the cache or the host bound";
+    case VS_STATUS_BAD_BLOCK: return "a block-table entry is outside the pool";
+    default: return "unknown status";
+    }
+}
+
+int32_t vs_tree_validate_host(const int32_t* parent, int32_t T) {
+    if (!parent) return VS_ERR_NULL;
+    if (T < 1 || T > VS_MAX_TREE) return VS_ERR_SHAPE;
+    return validate_tree_host(parent, T);
+}
+
+int32_t vs_tree_mask_build(const int32_t* parent, int32_t B, int32_t T, uint64_t* mask, int32_t* depth,
+                           int32_t* status, void* stream) {
+    if (!parent || !mask || !depth) return VS_ERR_NULL;
+    if (B < 1 || T < 1 || T > VS_MAX_TREE) return VS_ERR_SHAPE;
+    return launch_tree_mask(parent, B, T, mask, depth, status, (hipStream_t)stream) == hipSuccess ? VS_OK
+                                                                                                    : VS_ERR_HIP;
+}
+
+int32_t vs_attention_plan(const vs_attn_desc* desc, vs_attn_plan* plan) {
+    if (!plan) return VS_ERR_NULL;
+    const int32_t rc = check_desc(desc);
+    if (rc != VS_OK) return rc;
+    const Plan pl = make_plan(desc);
+    plan->impl = pl.impl;
+    plan->num_splits = pl.num_splits;
+    plan->keys_per_split = pl.keys_per_split;
+    plan->row_groups = pl.row_groups;
+    plan->waves_per_group = pl.waves;
+    plan->workgroups = pl.total_wgs;
+    plan->combine = (pl.impl == VS_IMPL_MFMA && pl.num_splits > 1) ? 1 : 0;
+    return VS_OK;
+}
+
+size_t vs_attention_workspace_bytes(const vs_attn_desc* desc) {
+    if (check_desc(desc) != VS_OK) return 0;
+    return workspace_bytes(desc, make_plan(desc));
+}
+
+int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const void* k_cache,
+                                 const void* v_cache, const int32_t* prefix_len, const int32_t* tree_parent,
+                                 const uint64_t* tree_mask, void* out, int32_t* status, void* workspace,
+                                 size_t workspace_bytes_given, void* stream) {
+    if (!desc || !q || !k_cache || !v_cache || !prefix_len || !tree_parent || !out) return VS_ERR_NULL;
+    const int32_t rc = check_desc(desc);
+    if (rc != VS_OK) return rc;
+    const Plan pl = make_plan(desc);
+    if (pl.impl == VS_IMPL_MFMA && !(aligned16(q) && aligned16(k_cache) && aligned16(v_cache) && aligned16(out)))
+        return VS_ERR_LAYOUT;
+    const size_t need = workspace_bytes(desc, pl);
+    if (need > 0 && (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))))
+        return VS_ERR_WORKSPACE;
+
+    AttnParams p{};
+    p.q = q;
+    p.k = k_cache;
+    p.v = v_cache;
+    p.out = out;
+    p.prefix_len = prefix_len;
+    p.parent = tree_parent;
+    p.tree_mask = tree_mask;
+    p.block_table = desc->paged ? desc->block_table : nullptr;
+    p.status = status;
+    p.B = desc->B;
+    p.T = desc->T;
+    p.Hq = desc->Hq;
+    p.Hkv = desc->Hkv;
+    p.d = desc->d;
+    p.group = desc->Hq / desc->Hkv;
+    p.rows = pl.rows;
+    p.rows_pad = pl.rows_pad;
+    p.max_prefix_len = desc->max_prefix_len;
+    p.paged = desc->paged ? 1 : 0;
+    p.block_size = desc->paged ? desc->block_size : 1;
+    p.block_shift = 0;
+    while ((1 << p.block_shift) < p.block_size) ++p.block_shift;
+    p.max_blocks = desc->max_blocks;
+    p.num_blocks = desc->num_blocks;
+    p.capacity = desc->capacity;
+    p.stride_seq = desc->stride_seq;
+    p.stride_block = desc->stride_block;
+    p.stride_head = desc->stride_head;
+    p.stride_tok = desc->stride_tok;
+    p.scale = desc->softmax_scale;
+    p.scale_log2 = desc->softmax_scale * 1.4426950408889634f;
+    p.num_splits = pl.num_splits;
+    p.keys_per_split = pl.keys_per_split;
+    p.row_groups = pl.row_groups;
+    p.rows_per_group = pl.waves * pl.rpw * kRowBlock;
+    p.total_wgs = pl.total_wgs;
+    if (need > 0) {
+        const size_t prow = (size_t)desc->B * desc->Hkv * pl.num_splits * pl.rows_pad;
+        p.part_o = (float*)workspace;
+        p.part_ml = (float*)((char*)workspace + align_up(prow * desc->d * sizeof(float)));
+    }
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (pl.impl == VS_IMPL_GENERIC) {
+        e = launch_attention_generic(p, desc->dtype, s);
+    } else {
+        e = launch_attention_mfma(p, pl.rpw, pl.waves, s);
+        if (e == hipSuccess && pl.num_splits > 1) e = launch_attention_combine(p, desc->dtype, s);
+    }
+    return e == hipSuccess ? VS_OK : VS_ERR_HIP;
+}
+
+size_t vs_accept_workspace_bytes(int32_t B, int32_t T, int32_t V) {
+    if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1) return 0;
+    const size_t n = (size_t)B * T * accept_chunks(V);
+    return align_up(n * sizeof(float)) + align_up(n * sizeof(int32_t));
+}
+
+int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V, const int32_t* draft_tokens,
+                       const int32_t* parent, int32_t B, int32_t T, int32_t* accepted_len, int32_t* path,
+                       int32_t* bonus_token, int32_t* row_argmax, int32_t* status, void* workspace,
+                       size_t workspace_bytes_given, void* stream) {
+    if (!logits || !draft_tokens || !parent || !accepted_len || !path || !bonus_token) return VS_ERR_NULL;
+    if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1 || ld_logits < V) return VS_ERR_SHAPE;
+    const size_t need = vs_accept_workspace_bytes(B, T, V);
+    if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;
+    AcceptParams p{};
+    p.logits = logits;
+    p.ld = ld_logits;
+    p.V = V;
+    p.draft = draft_tokens;
+    p.parent = parent;
+    p.B = B;
+    p.T = T;
+    p.accepted_len = accepted_len;
+    p.path = path;
+    p.bonus = bonus_token;
+    p.row_argmax = row_argmax;
+    p.status = status;
+    p.chunks = accept_chunks(V);
+    p.chunk_elems = kArgmaxChunk;
+    p.vec_ok = (aligned16(logits) && ld_logits % 4 == 0) ? 1 : 0;
+    const size_t n = (size_t)B * T * p.chunks;
+    p.part_val = (float*)workspace;
+    p.part_idx = (int32_t*)((char*)workspace + align_up(n * sizeof(float)));
+    return launch_accept(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
+}
+
+} // extern "C"

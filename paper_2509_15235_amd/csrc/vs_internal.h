@@ -1,0 +1,81 @@
+// Internal declarations shared by the HIP translation units of libvispec_verify.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "vispec_verify.h"
+
+namespace vs {
+
+constexpr int kWave = 64;
+constexpr int kTileKeys = 32;   // keys per LDS tile of the MFMA attention kernel
+constexpr int kRowBlock = 32;   // query rows per MFMA row block
+constexpr int kMaxWaves = 8;    // waves per workgroup in the MFMA attention kernel
+constexpr int kArgmaxBlock = 256;
+
+// Everything the attention kernels need, passed by value.
+struct AttnParams {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* out;
+    const int32_t* prefix_len;
+    const int32_t* parent;
+    const uint64_t* tree_mask;  // may be null
+    const int32_t* block_table; // paged only
+    int32_t* status;            // may be null
+    float* part_o;              // [unit][split][rows_pad][d] unnormalised partial outputs
+    float* part_ml;             // [unit][split][rows_pad][2] running max (log2 domain), sum
+    int32_t B, T, Hq, Hkv, d, group;
+    int32_t rows;               // T * group: query rows per (sequence, KV head)
+    int32_t rows_pad;           // rows rounded up to a multiple of kRowBlock
+    int32_t max_prefix_len;
+    int32_t paged, block_size, block_shift, max_blocks, num_blocks;
+    int64_t capacity;
+    int64_t stride_seq, stride_block, stride_head, stride_tok;
+    float scale;                // softmax scale
+    float scale_log2;           // softmax scale * log2(e)
+    int32_t num_splits;         // grid extent over key splits
+    int32_t keys_per_split;     // multiple of kTileKeys
+    int32_t row_groups;
+    int32_t rows_per_group;     // waves_per_group * row blocks per wave * kRowBlock
+    int32_t total_wgs;          // B * Hkv * num_splits * row_groups
+};
+
+struct AcceptParams {
+    const float* logits;
+    int64_t ld;
+    int32_t V;
+    const int32_t* draft;
+    const int32_t* parent;
+    int32_t B, T;
+    int32_t* accepted_len;
+    int32_t* path;
+    int32_t* bonus;
+    int32_t* row_argmax; // may be null
+    int32_t* status;     // may be null
+    float* part_val;     // [B*T][chunks]
+    int32_t* part_idx;   // [B*T][chunks]
+    int32_t chunks;
+    int32_t chunk_elems; // multiple of 4
+    int32_t vec_ok;      // rows are 16-byte aligned → float4 loads
+};
+
+// Shared tree check: returns a vs_status for lane-parallel use is in the kernels; this is
+// the scalar form used on the host.
+inline int32_t validate_tree_host(const int32_t* parent, int32_t T) {
+    if (parent[0] != -1) return VS_STATUS_BAD_ROOT;
+    for (int32_t i = 1; i < T; ++i)
+        if (parent[i] < 0 || parent[i] >= i) return VS_STATUS_BAD_PARENT;
+    return VS_STATUS_OK;
+}
+
+hipError_t launch_tree_mask(const int32_t* parent, int32_t B, int32_t T, uint64_t* mask,
+                            int32_t* depth, int32_t* status, hipStream_t s);
+hipError_t launch_attention_generic(const AttnParams& p, int dtype, hipStream_t s);
+hipError_t launch_attention_mfma(const AttnParams& p, int rpw, int waves, hipStream_t s);
+hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t s);
+hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
+
+} // namespace vs

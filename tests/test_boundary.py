@@ -1,0 +1,114 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2509_15235_amd as vs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "vispec_verify.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(vs_[a-z_]+)\s*\(", hdr))
+    assert declared == set(vs.EXPORTED_SYMBOLS)
+    L = ctypes.CDLL(vs.lib_path())
+    for name in declared:
+        assert hasattr(L, name), name
+    assert vs.vs_version() == 100
+
+
+def test_error_strings():
+    assert vs.vs_strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert vs.vs_strerror(code) not in ("ok", "unknown error")
+    assert vs.vs_strerror(-99) == "unknown error"
+    assert vs.vs_status_string(2).startswith("a parent")
+
+
+@pytest.mark.parametrize("parent,exp", [([-1], 0), ([-1, 0, 1, 1], 0), ([0], 1), ([-1, 1], 2), ([-1, 0, 2], 2),
+                                        ([-1, -1], 2), ([-1, 0, -5], 2)])
+def test_tree_validate_host(parent, exp):
+    a = np.array(parent, dtype=np.int32)
+    assert vs.vs_tree_validate_host(a, len(a)) == exp
+
+
+def test_tree_validate_host_matches_oracle_on_random_arrays(oracle_mod):
+    g = np.random.default_rng(0)
+    for _ in range(300):
+        T = int(g.integers(1, 10))
+        a = g.integers(-2, T, T).astype(np.int32)
+        if g.random() < 0.5:
+            a[0] = -1
+        assert vs.vs_tree_validate_host(a, T) == oracle_mod.tree_validate(a)
+    assert vs.vs_tree_validate_host(None, 3) == -1
+    assert vs.vs_tree_validate_host(np.array([-1], dtype=np.int32), 0) == -2
+    assert vs.vs_tree_validate_host(np.zeros(65, dtype=np.int32), 65) == -2
+
+
+def _desc(**kw):
+    d = vs.AttnDesc(B=1, T=60, Hq=28, Hkv=4, d=128, dtype=vs.VS_BF16, softmax_scale=0.1, max_prefix_len=1696,
+                    capacity=1800, stride_seq=4 * 1800 * 128, stride_head=1800 * 128, stride_tok=128)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+@pytest.mark.parametrize("kw,code", [
+    ({}, 0),
+    ({"T": 0}, -2), ({"T": 65}, -2), ({"B": 0}, -2), ({"Hq": 30}, -2), ({"d": 96}, -2),
+    ({"softmax_scale": 0.0}, -2), ({"softmax_scale": float("nan")}, -2), ({"max_prefix_len": -1}, -2),
+    ({"dtype": 7}, -3), ({"dtype": vs.VS_F32, "impl": vs.VS_IMPL_MFMA}, -3), ({"impl": 9}, -2),
+    ({"stride_tok": 64}, -6), ({"stride_tok": 132}, -6), ({"capacity": 1700}, -6),
+    ({"paged": 1, "block_size": 16, "max_blocks": 200, "num_blocks": 300, "stride_block": 4 * 16 * 128,
+      "stride_head": 16 * 128, "block_table": None}, -1),
+    ({"paged": 1, "block_size": 24, "max_blocks": 200, "num_blocks": 300, "block_table": 4096}, -6),
+    ({"paged": 1, "block_size": 16, "max_blocks": 10, "num_blocks": 300, "block_table": 4096}, -6),
+    ({"num_splits": -1}, -2),
+])
+def test_attention_descriptor_validation(kw, code):
+    rc, plan = vs.vs_attention_plan(_desc(**kw))
+    assert rc == code
+    if code != 0:
+        assert vs.vs_attention_workspace_bytes(_desc(**kw)) == 0
+
+
+def test_plan_and_workspace_sizes():
+    rc, plan = vs.vs_attention_plan(_desc())
+    assert rc == 0 and plan.impl == vs.VS_IMPL_MFMA and plan.waves_per_group == 8 and plan.row_groups == 1
+    assert plan.keys_per_split % 32 == 0 and plan.num_splits * plan.keys_per_split >= 1696 + 60
+    assert plan.workgroups == 4 * plan.num_splits
+    ws = vs.vs_attention_workspace_bytes(_desc())
+    assert ws >= 4 * plan.num_splits * 448 * 130 * 4
+    rc, plan1 = vs.vs_attention_plan(_desc(num_splits=1))
+    assert plan1.num_splits == 1 and plan1.combine == 0 and vs.vs_attention_workspace_bytes(_desc(num_splits=1)) == 0
+    rc, pg = vs.vs_attention_plan(_desc(dtype=vs.VS_F32))
+    assert pg.impl == vs.VS_IMPL_GENERIC and vs.vs_attention_workspace_bytes(_desc(dtype=vs.VS_F32)) == 0
+    rc, pm = vs.vs_attention_plan(_desc(Hq=32, Hkv=32, max_prefix_len=3136, capacity=3300))
+    assert pm.waves_per_group == 1 and pm.num_splits > 1
+
+
+def test_calls_reject_bad_arguments_before_any_launch():
+    d = _desc()
+    good = 4096  # never dereferenced: every call below fails validation first
+    assert vs.vs_tree_verify_attention(d, None, good, good, good, good, None, good) == -1
+    assert vs.vs_tree_verify_attention(d, good, good, good, good, good, None, None) == -1
+    assert vs.vs_tree_verify_attention(d, good + 2, good, good, good, good, None, good) == -6     # misaligned q
+    assert vs.vs_tree_verify_attention(d, good, good, good, good, good, None, good, None, None, 0) == -4
+    assert vs.vs_tree_verify_attention(d, good, good, good, good, good, None, good, None, good, 16) == -4
+    assert vs.vs_tree_verify_attention(_desc(T=99), good, good, good, good, good, None, good) == -2
+    assert vs.vs_tree_mask_build(None, 1, 4, good, good) == -1
+    assert vs.vs_tree_mask_build(good, 1, 65, good, good) == -2
+    assert vs.vs_tree_mask_build(good, 0, 4, good, good) == -2
+    n = vs.vs_accept_workspace_bytes(1, 60, 152064)
+    assert n >= 60 * 19 * 8
+    assert vs.vs_accept_workspace_bytes(1, 65, 10) == 0
+    assert vs.vs_tree_accept(None, 10, 10, good, good, 1, 4, good, good, good) == -1
+    assert vs.vs_tree_accept(good, 9, 10, good, good, 1, 4, good, good, good, None, None, good, 1 << 20) == -2
+    assert vs.vs_tree_accept(good, 10, 10, good, good, 1, 4, good, good, good, None, None, None, 0) == -4
+    assert vs.vs_tree_accept(good, 10, 10, good, good, 1, 4, good, good, good, None, None, good, 8) == -4

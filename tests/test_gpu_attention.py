@@ -1,0 +1,263 @@
+"""GPU parity of tree_verify_attention against the fp64 oracle.
+
+Contract tolerance (bf16 inputs, fp32 accumulation): |gpu - ref| <= 2e-2 + 1e-2 |ref|.
+Because that bound is loose next to outputs of rms ~0.04, every case also has to meet a
+tight bound derived from the arithmetic: the bf16 rounding of the output (2^-9 relative)
+plus the bf16 rounding of the probabilities (at most 2^-9 of the largest visible |V|, far
+less once hundreds of keys share the weight)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import gen
+import paper_2509_15235_amd as vs
+
+pytestmark = pytest.mark.gpu
+
+CONTRACT = (2e-2, 1e-2)
+TIGHT_LONG = (1.5e-3, 6e-3)    # hundreds of visible keys
+TIGHT_SHORT = (1.2e-2, 6e-3)   # a handful of keys: P's rounding is not averaged away
+TIGHT_F32 = (2e-5, 2e-5)
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import torch
+    assert torch.cuda.is_available()
+    import gpu_util
+    return gpu_util
+
+
+def _tight(inp):
+    if inp.cfg.dtype == "f32":
+        return TIGHT_F32
+    return TIGHT_LONG if int(inp.prefix_len.min()) >= 256 else TIGHT_SHORT
+
+
+def _run_and_check(gu, oracle_mod, inp, ref=None, **kw):
+    if ref is None:
+        ref = oracle_mod.tree_attention(inp, threads=8)
+    da = gu.DeviceAttn(inp, **kw)
+    got = da.run()
+    assert (da.status.cpu().numpy() == 0).all()
+    if inp.cfg.dtype == "bf16":
+        gu.check_close(got, ref, *CONTRACT, what="contract")
+    gu.check_close(got, ref, *_tight(inp), what=f"tight {kw}")
+    return got, ref, da
+
+
+# ---------------------------------------------------------------- the five configurations
+
+def test_c1_tiny_fp32(gu, oracle_mod):
+    inp = gen.attention_inputs(gen.CONFIGS["C1"], 11)
+    _run_and_check(gu, oracle_mod, inp)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+def test_full_size_single_sequence(gu, oracle_mod, name):
+    inp = gen.attention_inputs(gen.CONFIGS[name], 20 + int(name[1]))
+    ref = oracle_mod.tree_attention(inp, threads=8)
+    got, _, da = _run_and_check(gu, oracle_mod, inp, ref=ref)                       # launch shape of the bench
+    assert da.plan().impl == vs.VS_IMPL_MFMA
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=1)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=7)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
+
+
+def test_c5_ragged_paged_batch(gu, oracle_mod):
+    inp = gen.attention_inputs(gen.CONFIGS["C5"], 25)
+    ref = oracle_mod.tree_attention(inp, threads=8)
+    _run_and_check(gu, oracle_mod, inp, ref=ref)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=4)
+
+
+def test_layers_folded_into_batch(gu, oracle_mod):
+    """The bench's roofline launch: the layers of one C3 step as independent batch entries."""
+    cfg = dataclasses.replace(gen.CONFIGS["C3"], B=4, prefix=[1696] * 4)
+    inp = gen.attention_inputs(cfg, 26)
+    _run_and_check(gu, oracle_mod, inp)
+
+
+# ---------------------------------------------------------------- fuzz over shapes
+
+def _fuzz_cases():
+    cases = []
+    prefixes = [0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100, 257, 700]
+    k = 0
+    for d in (64, 128):
+        for g, hkv in ((1, 2), (2, 1), (4, 2), (7, 1), (8, 1)):
+            for paged in (False, True):
+                T = [1, 5, 33, 60, 64, 17, 2][k % 7]
+                S = prefixes[(3 * k) % len(prefixes)]
+                splits = [0, 1, 2, 3][k % 4]
+                B = 1 + k % 3
+                cases.append((d, g, hkv, paged, T, S, splits, B, k))
+                k += 1
+    return cases
+
+
+@pytest.mark.parametrize("d,g,hkv,paged,T,S,splits,B,k", _fuzz_cases())
+def test_fuzz_shapes(gu, oracle_mod, d, g, hkv, paged, T, S, splits, B, k):
+    depth = min(6, max(1, T - 1))
+    cfg = gen.Config(f"fuzz{k}", B, g * hkv, hkv, d, T, depth, 8, 100, 0.5, 1, "bf16",
+                     prefix=None if paged else [max(0, S - b) for b in range(B)],
+                     prefix_range=(max(0, S - 3), S + 40) if paged else None, paged=paged)
+    inp = gen.attention_inputs(cfg, 1000 + k)
+    ref = oracle_mod.tree_attention(inp, threads=4)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
+
+
+def test_paper_shaped_tree(gu, oracle_mod):
+    """Appendix A's tree: 30 draft tokens (31 nodes), depth 3, 8 nodes per expansion."""
+    parent = np.stack([gen.topk_tree(gen.rng(s, gen.STREAM_TREE)) for s in range(2)])
+    cfg = gen.Config("paper-tree", 2, 28, 4, 128, 31, 3, 8, 100, 0.5, 1, "bf16", prefix=[600, 333])
+    inp = gen.attention_inputs(cfg, 31, parent=parent)
+    _run_and_check(gu, oracle_mod, inp)
+
+
+# ---------------------------------------------------------------- mask-sensitive cases
+
+def test_tree_dominated_no_prefix(gu, oracle_mod):
+    """S = 0: every weight sits on tree keys, so a wrong mask bit cannot hide."""
+    for g, T in ((7, 60), (1, 64), (4, 9)):
+        cfg = gen.Config("nopre", 2, g, 1, 128, T, 6, 4, 100, 0.5, 1, "bf16", prefix=[0, 0])
+        inp = gen.attention_inputs(cfg, 40 + T)
+        _run_and_check(gu, oracle_mod, inp)
+        _run_and_check(gu, oracle_mod, inp, impl=vs.VS_IMPL_GENERIC)
+
+
+def test_mask_from_mask_build_equals_internal(gu, oracle_mod):
+    import torch
+    inp = gen.attention_inputs(dataclasses.replace(gen.CONFIGS["C3"], prefix=[50]), 41)
+    da = gu.DeviceAttn(inp)
+    a = da.run().copy()
+    _, _, _, mask_dev = gu.run_mask(inp.parent)
+    b = da.run(tree_mask=mask_dev)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("impl", [vs.VS_IMPL_MFMA, vs.VS_IMPL_GENERIC])
+def test_needles(gu, oracle_mod, impl):
+    """A huge key on a NON-ancestor tree slot must not move a node's output; the same key
+    on an ancestor slot must pull the output to that slot's value."""
+    S, T = 300, 24
+    cfg = gen.Config("needle", 1, 7, 1, 128, T, 5, 3, 100, 0.5, 1, "bf16", prefix=[S])
+    base = gen.attention_inputs(cfg, 42)
+    _, mask, _ = oracle_mod.tree_mask(base.parent[0])
+    node, head = T - 1, 3
+    non_anc = [j for j in range(T) if not (int(mask[node]) >> j & 1)]
+    anc = [j for j in range(T) if (int(mask[node]) >> j & 1)]
+    assert non_anc and len(anc) >= 2
+    ref_base = oracle_mod.tree_attention(base)
+
+    def planted(slot, val):
+        inp = gen.attention_inputs(cfg, 42)
+        kq = 4.0 * inp.q[0, node, head]                       # score ~ 4*|q|^2/sqrt(d) ~ 45
+        inp.k_cache[0, 0, S + slot] = kq
+        inp.v_cache[0, 0, S + slot] = val
+        inp.k_bits = gen.f32_to_bf16_bits(inp.k_cache)
+        inp.v_bits = gen.f32_to_bf16_bits(inp.v_cache)
+        inp.k_cache = gen.bf16_bits_to_f32(inp.k_bits)
+        inp.v_cache = gen.bf16_bits_to_f32(inp.v_bits)
+        return inp
+
+    inp = planted(non_anc[0], 100.0)
+    got = gu.DeviceAttn(inp, impl=impl).run()
+    gu.check_close(got[0, node, head], ref_base[0, node, head], *TIGHT_LONG, what="non-ancestor needle leaked")
+    inp = planted(anc[1], 100.0)
+    got = gu.DeviceAttn(inp, impl=impl).run()
+    ref = oracle_mod.tree_attention(inp)
+    assert abs(ref[0, node, head, 0] - 100.0) < 1.0
+    gu.check_close(got[0, node, head], ref[0, node, head], 0.5, 1e-2, what="ancestor needle")
+
+
+def test_redundant_image_keys_closed_form(gu):
+    """Paper Eq. 3-4 on the device: R identical keys + one unique key, T = 1."""
+    import math
+    d, R = 128, 2048
+    A, B = 0.0, math.log(512.0)
+    cfg = gen.Config("eq3", 1, 1, 1, d, 1, 1, 1, 10, 0.5, 1, "bf16", prefix=[R])
+    inp = gen.attention_inputs(cfg, 43)
+    q = np.zeros(d, dtype=np.float32); q[0] = 1.0
+    s = np.zeros(d, dtype=np.float32); s[0] = A
+    t = np.zeros(d, dtype=np.float32); t[0] = 6.25; t[5] = 3.0         # 6.25 is exact in bf16
+    B = 6.25
+    v_s = np.full(d, 0.5, dtype=np.float32)
+    v_t = np.full(d, -8.0, dtype=np.float32)
+    inp.q[0, 0, 0] = q
+    inp.k_cache[0, 0, :R + 1] = s
+    inp.v_cache[0, 0, :R + 1] = v_s
+    inp.k_cache[0, 0, 777] = t
+    inp.v_cache[0, 0, 777] = v_t
+    inp.scale = 1.0
+    for nm in ("q", "k", "v"):
+        arr = getattr(inp, nm if nm == "q" else nm + "_cache")
+        setattr(inp, nm + "_bits", gen.f32_to_bf16_bits(arr))
+    alpha = math.exp(B) / (R * math.exp(A) + math.exp(B))               # R redundant incl. the node's own key
+    expect = alpha * (-8.0) + (1 - alpha) * 0.5
+    for impl in (vs.VS_IMPL_MFMA, vs.VS_IMPL_GENERIC):
+        got = gu.DeviceAttn(inp, impl=impl, num_splits=3 if impl == vs.VS_IMPL_MFMA else 0).run()
+        np.testing.assert_allclose(got[0, 0, 0], expect, rtol=1e-2, atol=1e-2)
+
+
+# ---------------------------------------------------------------- layout and determinism
+
+def test_paged_equals_contiguous_bitwise(gu, oracle_mod):
+    cfg = dataclasses.replace(gen.CONFIGS["C5"], B=3, prefix_range=(900, 1400))
+    inp = gen.attention_inputs(cfg, 44)
+    da = gu.DeviceAttn(inp, num_splits=2)
+    paged = da.run().copy()
+    bs = cfg.block_size
+    # same tokens, gathered into a contiguous cache
+    cap = int(inp.prefix_len.max()) + cfg.T + 3
+    kb = np.full((cfg.B, cfg.Hkv, cap, cfg.d), gen.BF16_NAN_BITS, dtype=np.uint16)
+    vb = kb.copy()
+    for b in range(cfg.B):
+        n = int(inp.prefix_len[b]) + cfg.T
+        nb = (n + bs - 1) // bs
+        ids = inp.block_table[b, :nb]
+        kb[b, :, :n] = inp.k_bits[ids].transpose(1, 0, 2, 3).reshape(cfg.Hkv, nb * bs, cfg.d)[:, :n]
+        vb[b, :, :n] = inp.v_bits[ids].transpose(1, 0, 2, 3).reshape(cfg.Hkv, nb * bs, cfg.d)[:, :n]
+    cfg2 = dataclasses.replace(cfg, paged=False)
+    inp2 = gen.AttnInputs(cfg2, inp.prefix_len, inp.parent, inp.q, gen.bf16_bits_to_f32(kb), gen.bf16_bits_to_f32(vb),
+                          cap=cap, scale=inp.scale, q_bits=inp.q_bits, k_bits=kb, v_bits=vb)
+    cont = gu.DeviceAttn(inp2, num_splits=2).run()
+    assert np.array_equal(paged, cont)
+
+
+def test_deterministic_and_untouched_guards(gu):
+    import torch
+    inp = gen.attention_inputs(gen.CONFIGS["C3"], 45)
+    da = gu.DeviceAttn(inp)
+    a = da.run().copy()
+    da.out.fill_(float("nan"))
+    b = da.run()
+    assert np.array_equal(a, b)
+    assert np.isfinite(b).all()
+
+
+def test_max_prefix_bound_larger_than_actual(gu, oracle_mod):
+    """The host bound only sizes the launch: splits past a sequence's end are empty."""
+    cfg = dataclasses.replace(gen.CONFIGS["C3"], prefix=[130])
+    inp = gen.attention_inputs(cfg, 46, extra_cap=4000)
+    _run_and_check(gu, oracle_mod, inp, max_prefix_len=3000, num_splits=9)
+
+
+# ---------------------------------------------------------------- data-dependent errors
+
+def test_status_reports_bad_inputs_without_faulting(gu):
+    import torch
+    cfg = gen.Config("bad", 4, 4, 2, 64, 6, 3, 3, 10, 0.5, 1, "bf16", prefix_range=(20, 60), paged=True)
+    inp = gen.attention_inputs(cfg, 47)
+    inp.parent[1] = [-1, 0, 2, 1, 0, 0]            # parent[2] = 2 is not < 2
+    inp.prefix_len[2] = 10 ** 6                    # beyond the cache
+    inp.block_table[3, 0] = 10 ** 7                # outside the pool
+    for impl in (vs.VS_IMPL_MFMA, vs.VS_IMPL_GENERIC):
+        da = gu.DeviceAttn(inp, impl=impl, max_prefix_len=60)
+        da.run()
+        st = da.status.cpu().numpy()
+        assert list(st) == [0, 2, 3, 4], st
+        good = da.out[0].float().cpu().numpy()
+        assert np.isfinite(good).all()
