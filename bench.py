@@ -1,0 +1,283 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+A step = one pass of the whole path for one speculative cycle of the named workload:
+    1 x vs_tree_mask_build  +  L x vs_tree_verify_attention (one per decoder layer)
+    +  1 x vs_tree_accept
+over synthetic inputs already resident in HBM (seeded N(0,1) Q/K/V, logits with planted
+matches; they stand in for the paper's benchmark prompts and model weights). Projections,
+RoPE, MLPs and the LM head are not part of the step.
+
+Prints ONE JSON line: verify steps/s as `value`, plus
+  roofline      the attention kernel with the step's L layers folded into one launch as
+                independent batch entries (same per-layer shape), timed with HIP events
+  per_layer_call  the same kernel launched for a single layer (B = 1), launch-bound
+  argmax        the logits scan of vs_tree_accept against HBM bandwidth
+  cpu_baseline  the fp64 CPU oracle timed on this machine's host cores
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C3", choices=["C2", "C3", "C4"])
+    ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate over (0 = enough to exceed 512 MB)")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue every launch from Python instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--folded-splits", type=int, default=0)
+    ap.add_argument("--seed", type=int, default=2024)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no cross-GPU part); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import gen
+    import paper_2509_15235_amd as vs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    vs.lib()  # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = gen.CONFIGS[args.config]
+    L, T, Hq, Hkv, d, V = cfg.layers, cfg.T, cfg.Hq, cfg.Hkv, cfg.d, cfg.V
+    S = int(cfg.prefix[0])
+    group = Hq // Hkv
+    cap = S + T + 4
+    scale = 1.0 / np.sqrt(d)
+    eb = 2
+
+    # ---------------------------------------------------------------- inputs
+    parent_h = gen.draw_trees(cfg, args.seed)                       # [1, T]
+    host_layers = [gen.attention_inputs(cfg, args.seed, layer=l, poison_tail=False, parent=parent_h, extra_cap=4)
+                   for l in range(L)]
+    acc_h = gen.accept_inputs(cfg, args.seed, parent=parent_h)
+
+    kv_bytes_set = 2 * L * Hkv * cap * d * eb
+    logit_bytes = T * V * 4
+    nsets = args.sets if args.sets > 0 else max(2, int(np.ceil(600e6 / (kv_bytes_set + logit_bytes))))
+
+    def bf16_dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    gtorch = torch.Generator(device=dev)
+    gtorch.manual_seed(args.seed)
+    sets = []
+    for s in range(nsets):
+        if s == 0:
+            q = bf16_dev(np.concatenate([h.q_bits for h in host_layers], axis=0))          # [L,T,Hq,d]
+            k = bf16_dev(np.concatenate([h.k_bits for h in host_layers], axis=0))          # [L,Hkv,cap,d]
+            v = bf16_dev(np.concatenate([h.v_bits for h in host_layers], axis=0))
+            logits = torch.from_numpy(acc_h.logits[0]).to(dev)                             # [T,V]
+        else:
+            q = torch.randn((L, T, Hq, d), generator=gtorch, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            k = torch.randn((L, Hkv, cap, d), generator=gtorch, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            v = torch.randn((L, Hkv, cap, d), generator=gtorch, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            logits = torch.randn((T, V), generator=gtorch, device=dev, dtype=torch.float32)
+        out = torch.empty((L, T, Hq, d), device=dev, dtype=torch.bfloat16)
+        sets.append(dict(q=q, k=k, v=v, out=out, logits=logits))
+
+    parent1 = torch.from_numpy(parent_h.astype(np.int32)).to(dev)                          # [1,T]
+    parentL = parent1.repeat(L, 1).contiguous()                                            # [L,T]
+    prefix1 = torch.full((1,), S, device=dev, dtype=torch.int32)
+    prefixL = torch.full((L,), S, device=dev, dtype=torch.int32)
+    tokens = torch.from_numpy(acc_h.tokens.astype(np.int32)).to(dev)
+    mask = torch.zeros((1, T), device=dev, dtype=torch.int64)
+    maskL = torch.zeros((L, T), device=dev, dtype=torch.int64)
+    depth = torch.zeros((L, T), device=dev, dtype=torch.int32)
+    status = torch.zeros((L,), device=dev, dtype=torch.int32)
+    alen = torch.zeros((1,), device=dev, dtype=torch.int32)
+    path = torch.zeros((1, T), device=dev, dtype=torch.int32)
+    bonus = torch.zeros((1,), device=dev, dtype=torch.int32)
+    amax = torch.zeros((1, T), device=dev, dtype=torch.int32)
+
+    def make_desc(B, num_splits):
+        dsc = vs.AttnDesc(B=B, T=T, Hq=Hq, Hkv=Hkv, d=d, dtype=vs.VS_BF16, softmax_scale=float(scale),
+                          max_prefix_len=S, paged=0, capacity=cap, stride_seq=Hkv * cap * d,
+                          stride_head=cap * d, stride_tok=d, impl=vs.VS_IMPL_AUTO, num_splits=num_splits)
+        return dsc
+
+    desc1 = make_desc(1, args.num_splits)
+    descL = make_desc(L, args.folded_splits)
+    rc1, plan1 = vs.vs_attention_plan(desc1)
+    rcL, planL = vs.vs_attention_plan(descL)
+    assert rc1 == 0 and rcL == 0
+    ws_bytes = max(vs.vs_attention_workspace_bytes(desc1), vs.vs_attention_workspace_bytes(descL), 256)
+    ws = torch.empty(ws_bytes, device=dev, dtype=torch.uint8)
+    aws_bytes = vs.vs_accept_workspace_bytes(1, T, V)
+    aws = torch.empty(aws_bytes, device=dev, dtype=torch.uint8)
+    lay_q = T * Hq * d * eb
+    lay_kv = Hkv * cap * d * eb
+
+    def check(rc):
+        if rc != 0:
+            raise vs.VSError(rc, "libvispec_verify")
+
+    def enqueue_step(st, stream):
+        check(vs.vs_tree_mask_build(parent1, 1, T, mask, depth, status, stream))
+        qp, kp, vp, op = st["q"].data_ptr(), st["k"].data_ptr(), st["v"].data_ptr(), st["out"].data_ptr()
+        for l in range(L):
+            check(vs.vs_tree_verify_attention(desc1, qp + l * lay_q, kp + l * lay_kv, vp + l * lay_kv, prefix1,
+                                              parent1, mask, op + l * lay_q, status, ws, ws_bytes, stream))
+        check(vs.vs_tree_accept(st["logits"], V, V, tokens, parent1, 1, T, alen, path, bonus, amax, status,
+                                aws, aws_bytes, stream))
+
+    def enqueue_folded(st, stream):
+        check(vs.vs_tree_verify_attention(descL, st["q"], st["k"], st["v"], prefixL, parentL, maskL, st["out"],
+                                          status, ws, ws_bytes, stream))
+
+    def enqueue_accept(st, stream):
+        check(vs.vs_tree_accept(st["logits"], V, V, tokens, parent1, 1, T, alen, path, bonus, amax, status,
+                                aws, aws_bytes, stream))
+
+    stream = torch.cuda.Stream(device=dev)
+    sp = stream.cuda_stream
+    check(vs.vs_tree_mask_build(parentL, L, T, maskL, depth, status, sp))
+    stream.synchronize()
+
+    # ---------------------------------------------------------------- parity spot check (layer 0 of set 0)
+    import oracle
+    with torch.cuda.stream(stream):
+        enqueue_step(sets[0], sp)
+    stream.synchronize()
+    ref0 = oracle.tree_attention(host_layers[0], threads=min(os.cpu_count() or 1, 16))
+    got0 = sets[0]["out"][0].float().cpu().numpy()
+    err0 = float(np.abs(got0 - ref0[0]).max())
+    o_amax, o_alen, o_path, o_bonus = oracle.tree_accept(acc_h.logits, acc_h.tokens, acc_h.parent)
+    accept_ok = bool((amax.cpu().numpy() == o_amax).all() and alen.item() == o_alen[0] and bonus.item() == o_bonus[0]
+                     and (path.cpu().numpy() == o_path).all())
+    if not (err0 <= 2e-2 and accept_ok):
+        print(f"bench.py: parity check failed (attention max|err| {err0}, accept ok {accept_ok})", file=sys.stderr)
+        sys.exit(4)
+
+    # ---------------------------------------------------------------- runners (HIP graphs or eager)
+    def build_runner(enq):
+        if args.no_graph:
+            return [(lambda st=st: enq(st, sp)) for st in sets]
+        graphs = []
+        for st in sets:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                enq(st, torch.cuda.current_stream().cuda_stream)
+            graphs.append(g)
+        return [g.replay for g in graphs]
+
+    def timed(runner, iters, warmup):
+        with torch.cuda.stream(stream):
+            for i in range(warmup):
+                runner[i % nsets]()
+            stream.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record(stream)
+            for i in range(iters):
+                runner[i % nsets]()
+            e1.record(stream)
+            stream.synchronize()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+        return e0.elapsed_time(e1) / iters, wall / iters * 1e3            # ms per iteration (events, wall clock)
+
+    step_runner = build_runner(enqueue_step)
+    ms_step, ms_step_wall = timed(step_runner, args.steps, args.warmup)
+    ms_step = max(ms_step, ms_step_wall) if args.no_graph else ms_step
+
+    folded_runner = build_runner(enqueue_folded)
+    ms_folded, _ = timed(folded_runner, max(args.steps, 50), max(args.warmup, 5))
+
+    def enqueue_one_layer(st, stream_):
+        check(vs.vs_tree_verify_attention(desc1, st["q"], st["k"], st["v"], prefix1, parent1, mask, st["out"],
+                                          status, ws, ws_bytes, stream_))
+    single_runner = build_runner(enqueue_one_layer)
+    ms_single, _ = timed(single_runner, max(args.steps, 50) * 4, max(args.warmup, 5))
+
+    accept_runner = build_runner(enqueue_accept)
+    ms_accept, _ = timed(accept_runner, max(args.steps, 50), max(args.warmup, 5))
+
+    # ---------------------------------------------------------------- algorithmic work
+    _, _, depth_h = oracle.tree_mask(parent_h[0])
+    vis_pairs = int(sum(S + int(dd) + 1 for dd in depth_h))                      # visible (query, key) pairs per head
+    flops_layer = 4.0 * d * Hq * vis_pairs
+    bytes_layer = 2.0 * Hkv * (S + T) * d * eb + 2.0 * T * Hq * d * eb
+    t_mfma = flops_layer / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    t_hbm = bytes_layer / (HBM_PEAK_GBS * 1e9)
+    bound = "mfma" if t_mfma >= t_hbm else "hbm"
+
+    def roof(ms_call, layers_per_call):
+        sec = ms_call * 1e-3
+        if bound == "mfma":
+            ach = flops_layer * layers_per_call / sec / 1e12
+            return {"bound": "mfma", "achieved": round(ach, 3), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+        ach = bytes_layer * layers_per_call / sec / 1e9
+        return {"bound": "hbm", "achieved": round(ach, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+
+    roofline = roof(ms_folded, L)
+    roofline.update({"kernel": "attn_mfma_kernel (+ split combine)", "launch": f"{L} layers folded as batch entries",
+                     "us_per_launch": round(ms_folded * 1e3, 2), "workgroups": planL.workgroups,
+                     "num_splits": planL.num_splits,
+                     "tflops": round(flops_layer * L / (ms_folded * 1e-3) / 1e12, 2),
+                     "hbm_gbs": round(bytes_layer * L / (ms_folded * 1e-3) / 1e9, 1),
+                     "frac_of_hbm_peak": round(bytes_layer * L / (ms_folded * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+    per_layer = roof(ms_single, 1)
+    per_layer.update({"launch": "one layer, B=1", "us_per_launch": round(ms_single * 1e3, 2),
+                      "workgroups": plan1.workgroups, "num_splits": plan1.num_splits})
+    argmax_gbs = logit_bytes / (ms_accept * 1e-3) / 1e9
+    argmax = {"bound": "hbm", "achieved": round(argmax_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+              "frac": round(argmax_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(ms_accept * 1e3, 2),
+              "bytes": logit_bytes}
+
+    # ---------------------------------------------------------------- CPU baseline: the oracle, one full step
+    cpu = None
+    if not args.no_cpu_baseline:
+        threads = min(os.cpu_count() or 1, 16, Hq)
+        t0 = time.perf_counter()
+        for l in range(L):
+            oracle.tree_attention(host_layers[l], threads=threads)
+        oracle.tree_accept(acc_h.logits, acc_h.tokens, acc_h.parent)
+        tc = time.perf_counter() - t0
+        cpu = {"value": round(1.0 / tc, 4), "unit": "steps/s", "cores": threads, "kind": "oracle",
+               "sample": f"one full step of {cfg.name}: {L} layers of fp64 attention + one accept, {tc:.2f} s"}
+
+    line = {
+        "metric": "verify steps/sec (tree-verify attention TFLOP/s and HBM GB/s as % of roofline in `roofline`)",
+        "value": round(1e3 / ms_step, 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B=1 Hq={Hq} Hkv={Hkv} d={d} prefix={S} tree={T} nodes depth<={cfg.max_depth} "
+                               f"layers={L} vocab={V}; step = mask_build + {L} x attention + accept",
+                   "hip_graph": not args.no_graph, "buffer_sets": nsets},
+        "roofline": roofline, "per_layer_call": per_layer, "argmax": argmax, "cpu_baseline": cpu,
+        "parity": {"attention_max_abs_err_layer0": err0, "accept_bit_exact": accept_ok},
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
