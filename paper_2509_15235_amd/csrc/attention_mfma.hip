@@ -8,51 +8,84 @@
 // the contraction against that head's keys is a dense [rows x d] x [d x keys] product.
 // One workgroup owns (sequence, KV head, key split, row group); each of its NW waves
 // owns RPW blocks of 32 rows and keeps their queries, running softmax state and output
-// accumulators in registers for the whole key range. Keys stream through LDS in tiles
-// of 32: K as stored ([key][d]), V transposed ([d][key]).
+// accumulators in registers for the whole key range. Keys stream through double-buffered
+// LDS tiles of 32 keys that are filled by direct global-to-LDS loads (no staging
+// registers); the 16-byte chunks of K and V are placed so that reads are conflict-free.
 //
 // Per tile and row block (v_mfma_f32_32x32x16_bf16, A = 32x16, B = 16x32, C = 32x32):
 //   S^T[key][row] = K[key][:] . Q[row][:]        A = K tile (LDS), B = Q (registers)
 //   online softmax along keys: a lane holds 16 keys of ONE row, so the row's ancestor
 //   mask, running max and running sum are plain per-lane scalars
-//   O^T[d][row] += V^T[d][key] . P^T[key][row]   A = V^T tile (LDS), B = P (registers:
-//   the C layout of S^T is, after rounding to bf16, already a B operand; V^T is stored
-//   in LDS with the matching key order)
+//   O^T[d][row] += V^T[d][key] . P^T[key][row]   A = V^T (ds_read_b64_tr_b16 transposes
+//   the row-major V tile on its way out of LDS), B = P (registers: the C layout of S^T
+//   is, after rounding to bf16, already a B operand; the V reads pick keys in that order)
 //
 // With one split the normalised result is written as bf16; otherwise unnormalised
-// partials (O, running max, running sum) go to the workspace for the combine kernel.
+// partials (O, running max, running sum) go to the workspace, laid out exactly as the
+// accumulator registers are (so every store is a contiguous 1 KB per wave), and the
+// combine kernel merges them.
+#include <type_traits>
+
 #include "vs_device.h"
 
 namespace vs {
 
 namespace {
 
-constexpr int kKPad = 8; // bf16 elements of padding per LDS row (keeps 16-byte reads conflict-free)
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-// Position of tile-local key `key` (0..31) inside a V^T row. The MFMA C layout gives
-// lane half h of a 32x32 block keys {8a + 4h + c}; as a B operand that lane must hold 8
-// consecutive contraction indices, so keys are stored with bits a (8s) and h (4s) swapped.
-__device__ __forceinline__ int vt_pos(int key) {
-    return (key & 16) | ((key & 4) << 1) | ((key & 8) >> 1) | (key & 3);
+typedef __attribute__((address_space(3))) void lds_void;
+
+// s_waitcnt immediate that waits for every outstanding vector-memory load (vmcnt = 0) and
+// nothing else (expcnt = 7, lgkmcnt = 15 are their maxima).
+constexpr int kWaitVm0 = 0x0F70;
+
+// max / sum over the two 32-lane halves, result in every lane (v_permlane32_swap)
+__device__ __forceinline__ float half_max(float x) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Partial results of one (sequence, KV head, split, 32-row block): D/32 accumulator blocks,
+// each stored as 4 x [64 lanes x 4 floats] (register r = 4*q4 + e of lane l at
+// ((db*4 + q4)*64 + l)*4 + e), followed elsewhere by 32 x (max, sum).
+__device__ __forceinline__ int64_t part_block(const AttnParams& p, int64_t unit, int split, int rbk) {
+    return (unit * p.num_splits + split) * (int64_t)(p.rows_pad / kRowBlock) + rbk;
 }
 
 template <int D, int RPW, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) {
-    constexpr int NT = NW * kWave;
-    constexpr int KS = D / 16;              // k-steps of the S^T product
-    constexpr int DB = D / 32;              // 32-channel blocks of the output
-    constexpr int CPR = D / 8;              // 16-byte chunks per key row
-    constexpr int CHUNKS = kTileKeys * CPR; // chunks per K (or V) tile
-    constexpr int CPT = (CHUNKS + NT - 1) / NT;
+    constexpr int KS = D / 16;               // k-steps of the S^T product
+    constexpr int DB = D / 32;               // 32-channel blocks of the output
+    constexpr int TILE = kTileKeys * D;      // elements per K (or V) tile
+    constexpr int IPT = TILE * 2 / 1024;     // 1 KB direct-to-LDS load instructions per tile
+    constexpr int IPW = (IPT + NW - 1) / NW; // ... issued by each wave
+    // Two row blocks per wave at two waves per SIMD (256 registers each) do not leave room
+    // for both blocks' queries next to the accumulators: the second block's query
+    // fragments then live in a lane-private LDS slot (written once, by a direct load)
+    // instead of being spilled to scratch memory by the compiler.
+    constexpr bool QL = (RPW == 2 && NW == 8);
 
-    __shared__ __attribute__((aligned(16))) uint16_t sK[kTileKeys][D + kKPad];
-    __shared__ __attribute__((aligned(16))) uint16_t sVt[D][kTileKeys + kKPad];
+    // Tiles live in LDS in 16-byte chunks placed so that every access is conflict-free and
+    // every address is "per-lane constant + immediate". A direct-to-LDS load instruction
+    // writes lane q's 16 bytes at (1 KB block i) + 16 q, and each lane may fetch any chunk:
+    //   K: block i, lane q holds row 16*(i / (D/32)) + q%16, chunk (D/32 == 4 ? 4*(i%4) : 4*(i%2)) + q/16
+    //   V: block i, lane q holds row 16*(i / (D/32)) + 4*(q/16) + (q%16)/4, chunk 4*(i % (D/32)) + q%4
+    __shared__ __attribute__((aligned(1024))) uint16_t sK[2][TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t sV[2][TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t sQ[QL ? NW * KS * 512 : 8];
     __shared__ int32_t sp[VS_MAX_TREE];
     __shared__ int32_t sflag;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // wave-uniform, lives in an SGPR
     const int half = lane >> 5;
     const int col = lane & 31;
 
@@ -80,6 +113,41 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     if (k0 >= nk) return;
     const int k1 = min(nk, k0 + p.keys_per_split);
 
+    // ---- asynchronous global -> LDS copy of one K/V tile (no registers in between).
+    // Load block i covers the 16 tokens r0 .. r0+15 (r0 a multiple of 16, so one cache
+    // block in paged mode) and 32 channels. Tokens past the last valid one re-read that
+    // last token: finite values that the mask turns into zero weights.
+    const uint16_t* kbase = (const uint16_t*)p.k;
+    const uint16_t* vbase = (const uint16_t*)p.v;
+    const int64_t head_base = (p.paged ? 0 : (int64_t)b * p.stride_seq) + (int64_t)kvh * p.stride_head;
+    const int stride_tok = (int)p.stride_tok;           // host guarantees 32-bit lane offsets
+    const int krow_l = lane & 15, kcol_l = (lane >> 4) * 8;
+    const int vrow_l = 4 * (lane >> 4) + ((lane & 15) >> 2), vcol_l = (lane & 3) * 8;
+    auto fetch = [&](int kt, int buf) {
+#pragma unroll
+        for (int j = 0; j < IPW; ++j) {
+            const int i = wave * IPW + j; // block index, uniform per wave
+            if (i < IPT) {
+                const int r0 = kt + 16 * (i / DB);
+                const int c0 = 32 * (i % DB);
+                int ktok = min(r0 + krow_l, k1 - 1), vtok = min(r0 + vrow_l, k1 - 1);
+                int64_t base = head_base;
+                if (p.paged) {
+                    int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (min(r0, k1 - 1) >> p.block_shift)];
+                    if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
+                    base += (int64_t)blk * p.stride_block;
+                    ktok &= p.block_size - 1;
+                    vtok &= p.block_size - 1;
+                }
+                const uint32_t koff = (uint32_t)(ktok * stride_tok + c0 + kcol_l);
+                const uint32_t voff = (uint32_t)(vtok * stride_tok + c0 + vcol_l);
+                __builtin_amdgcn_global_load_lds(kbase + base + koff, (lds_void*)(sK[buf] + i * 512), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(vbase + base + voff, (lds_void*)(sV[buf] + i * 512), 16, 0, 0);
+            }
+        }
+    };
+    fetch(k0, 0); // in flight while the queries are loaded
+
     // ---- this wave's rows, their masks and queries
     const int row_base = rg * p.rows_per_group + wave * (RPW * kRowBlock);
     const bool wave_active = row_base < p.rows;
@@ -88,19 +156,20 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     const uint16_t* qbase = (const uint16_t*)p.q;
 #pragma unroll
     for (int rb = 0; rb < RPW; ++rb) {
-        const int r = row_base + rb * kRowBlock + col;
-        mask[rb] = 0;
-        if (r < p.rows) {
-            const int node = r / p.group;
-            const int hq = kvh * p.group + (r - node * p.group);
-            mask[rb] = p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node);
-            const uint16_t* qr = qbase + (((int64_t)b * p.T + node) * p.Hq + hq) * D + half * 8;
+        // rows past the end repeat the last row (finite data, results discarded)
+        const int r = min(row_base + rb * kRowBlock + col, p.rows - 1);
+        const int node = r / p.group;
+        const int hq = kvh * p.group + (r - node * p.group);
+        mask[rb] = p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node);
+        const uint16_t* qr = qbase + (((int64_t)b * p.T + node) * p.Hq + hq) * D + half * 8;
+        if (wave_active) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                qf[rb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qr + ks * 16));
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) qf[rb][ks] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+            for (int ks = 0; ks < KS; ++ks) {
+                if (QL && rb == 1)
+                    __builtin_amdgcn_global_load_lds(qr + ks * 16, (lds_void*)(sQ + (wave * KS + ks) * 512), 16, 0, 0);
+                else
+                    qf[rb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qr + ks * 16));
+            }
         }
     }
 
@@ -116,80 +185,59 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
             for (int r = 0; r < 16; ++r) acc[rb][db][r] = 0.f;
     }
 
-    const uint16_t* kbase = (const uint16_t*)p.k;
-    const uint16_t* vbase = (const uint16_t*)p.v;
-    u32x4 kreg[CPT], vreg[CPT];
+    // per-lane LDS offsets (elements); everything else is a compile-time immediate
+    const int k_lane = (col >> 4) * (DB * 512) + half * 128 + (col & 15) * 8; // + ks*256
+    const int t16 = lane & 15;                                               // transposing V read: 16-lane groups
+    const int v_lane = half * 128 + (t16 >> 2) * 32 + ((lane >> 4) & 1) * 16 + ((t16 >> 1) & 1) * 8 + (t16 & 1) * 4;
+    //                 + sl*(DB*512) + db*512 + u*256
+    const uint16_t* q_lane = sQ + wave * (KS * 512) + lane * 8;              // + ks*512
 
-    auto fetch = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            const int c = tid + i * NT;
-            kreg[i] = u32x4{0, 0, 0, 0};
-            vreg[i] = u32x4{0, 0, 0, 0};
-            if (c < CHUNKS) {
-                const int key = c / CPR, dc = c % CPR;
-                const int tok = kt + key;
-                if (tok < k1) { // slots past the last valid token stay zero in LDS
-                    const int64_t off = token_offset(p, b, kvh, tok) + dc * 8;
-                    kreg[i] = *(const u32x4*)(kbase + off);
-                    vreg[i] = *(const u32x4*)(vbase + off);
-                }
-            }
-        }
-    };
-    auto stash = [&]() {
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            const int c = tid + i * NT;
-            if (c < CHUNKS) {
-                const int key = c / CPR, dc = c % CPR;
-                *(u32x4*)&sK[key][dc * 8] = kreg[i];
-                const int pos = vt_pos(key);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    sVt[dc * 8 + 2 * e][pos] = (uint16_t)(vreg[i][e] & 0xffffu);
-                    sVt[dc * 8 + 2 * e + 1][pos] = (uint16_t)(vreg[i][e] >> 16);
-                }
-            }
-        }
-    };
-
-    fetch(k0);
-    for (int kt = k0; kt < k1; kt += kTileKeys) {
-        __syncthreads(); // previous tile fully consumed
-        stash();
-        __syncthreads();
-        if (kt + kTileKeys < k1) fetch(kt + kTileKeys); // in flight while this tile is computed
-        if (!wave_active) continue;
-
+    // One 32-key tile for this wave's row blocks. MASKED tiles hold tree slots or the end
+    // of the key range; all others are pure prefix and skip the visibility logic.
+    auto tile = [&](auto masked_tag, int kt, int buf) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const uint16_t* tK = sK[buf] + k_lane;
+        const uint16_t* tV = sV[buf] + v_lane;
         // ---- per row block: S^T = K . Q^T, mask, online softmax, P as a B operand.
         // Lane (col, half) holds keys 8*(r/4) + 4*half + r%4 of row `col`.
-        const bool need_mask = (kt + kTileKeys > S) || (kt + kTileKeys > k1);
+        // Each K fragment is read from LDS once and feeds every row block.
+        f32x16 sc[RPW];
+#pragma unroll
+        for (int rb = 0; rb < RPW; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc[rb][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(tK + ks * 256));
+#pragma unroll
+            for (int rb = 0; rb < RPW; ++rb) {
+                const bf16x8 bq = (QL && rb == 1) ? __builtin_bit_cast(bf16x8, *(const u32x4*)(q_lane + ks * 512))
+                                                  : qf[rb][ks];
+                sc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq, sc[rb], 0, 0, 0);
+            }
+        }
         bf16x8 pf[RPW][2];
 #pragma unroll
         for (int rb = 0; rb < RPW; ++rb) {
-            f32x16 s;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sK[col][ks * 16 + half * 8]);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][ks], s, 0, 0, 0);
-            }
-            if (need_mask) {
+            f32x16& s = sc[rb];
+            if constexpr (MASKED) {
+                const int rel = kt + 4 * half - S; // tree slot of this lane's key 0 (negative: prefix)
+                const uint32_t tree_end = (uint32_t)(k1 - S);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int kabs = kt + 8 * (r >> 2) + 4 * half + (r & 3);
-                    const bool vis = (kabs < S) || (kabs < k1 && ((mask[rb] >> ((kabs - S) & 63)) & 1ull));
+                    const int sh = rel + 8 * (r >> 2) + (r & 3);
+                    const uint32_t bit = (uint32_t)(mask[rb] >> (sh & 63)) & 1u;
+                    const bool vis = (sh < 0) | (((uint32_t)sh < tree_end) & (bit != 0));
                     s[r] = vis ? s[r] : -INFINITY;
                 }
             }
-            float mx = s[0];
+            float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
-            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
+            mx = fmaxf(mx, s[15]);
+            mx = half_max(mx);
             const float m_new = fmaxf(m2[rb], mx * p.scale_log2);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new; // no visible key yet
+            const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new; // no visible key yet
             const float alpha = __builtin_amdgcn_exp2f(m2[rb] - m_use);
             m2[rb] = m_new;
             float psum = 0.f;
@@ -217,18 +265,42 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
             }
         }
 
-        // ---- O^T += V^T . P^T
+        // ---- O^T += V^T . P^T. The A operand (channel `col` of block db, keys in the
+        // order P holds them) comes from two transposing reads of 4 keys x 16 channels.
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl) {
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const bf16x8 a =
-                    __builtin_bit_cast(bf16x8, *(const u32x4*)&sVt[db * 32 + col][sl * 16 + half * 8]);
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tV + sl * (DB * 512) + db * 512));
+                const s16x4 hi =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tV + sl * (DB * 512) + db * 512 + 256));
+                const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
                 for (int rb = 0; rb < RPW; ++rb)
                     acc[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[rb][sl], acc[rb][db], 0, 0, 0);
             }
         }
+    };
+
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __syncthreads();
+
+    // Tiles that end at or before min(S, k1) are pure prefix; the rest need the mask.
+    const int k_plain = k0 + max(0, (min(S, k1) - k0) / kTileKeys) * kTileKeys;
+    int buf = 0;
+    int kt = k0;
+    for (; kt < k_plain; kt += kTileKeys, buf ^= 1) {
+        // the other buffer's last readers passed the barrier that ended the previous iteration
+        if (kt + kTileKeys < k1) fetch(kt + kTileKeys, buf ^ 1);
+        if (wave_active) tile(std::false_type{}, kt, buf);
+        __builtin_amdgcn_s_waitcnt(kWaitVm0); // the next tile has landed in LDS ...
+        __syncthreads();                      // ... and everyone is done with this one
+    }
+    for (; kt < k1; kt += kTileKeys, buf ^= 1) {
+        if (kt + kTileKeys < k1) fetch(kt + kTileKeys, buf ^ 1);
+        if (wave_active) tile(std::true_type{}, kt, buf);
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        __syncthreads();
     }
 
     if (!wave_active) return;
@@ -237,9 +309,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
 #pragma unroll
     for (int rb = 0; rb < RPW; ++rb) {
         const int r_local = row_base + rb * kRowBlock + col;
-        const float l = lsum[rb] + __shfl_xor(lsum[rb], 32);
-        if (r_local >= p.rows) continue;
+        const float l = half_sum(lsum[rb]);
         if (p.num_splits == 1) {
+            if (r_local >= p.rows) continue;
             const int node = r_local / p.group;
             const int hq = kvh * p.group + (r_local - node * p.group);
             uint16_t* o = (uint16_t*)p.out + (((int64_t)b * p.T + node) * p.Hq + hq) * D;
@@ -254,66 +326,86 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
                     *(u32x2*)(o + db * 32 + 8 * q4 + 4 * half) = w;
                 }
         } else {
-            const int64_t unit = (int64_t)b * p.Hkv + kvh;
-            const int64_t prow = (unit * p.num_splits + split) * p.rows_pad + r_local;
-            float* po = p.part_o + prow * D;
+            if (row_base + rb * kRowBlock >= p.rows) continue; // whole block is padding
+            const int64_t blk = part_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
+            float* po = p.part_o + blk * (kRowBlock * D) + lane * 4;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    f32x4 w = {acc[rb][db][4 * q4], acc[rb][db][4 * q4 + 1], acc[rb][db][4 * q4 + 2],
-                               acc[rb][db][4 * q4 + 3]};
-                    *(f32x4*)(po + db * 32 + 8 * q4 + 4 * half) = w;
+                    const f32x4 w = {acc[rb][db][4 * q4], acc[rb][db][4 * q4 + 1], acc[rb][db][4 * q4 + 2],
+                                     acc[rb][db][4 * q4 + 3]};
+                    __builtin_nontemporal_store(w, (f32x4*)(po + (db * 4 + q4) * 256));
                 }
             if (half == 0) {
-                p.part_ml[prow * 2] = m2[rb];
-                p.part_ml[prow * 2 + 1] = l;
+                const f32x2 ml = {m2[rb], l};
+                *(f32x2*)(p.part_ml + (blk * kRowBlock + col) * 2) = ml;
             }
         }
     }
 }
 
-// Merges the key splits of one query row: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-// grid = (ceil(rows / RPB), B * Hkv), block = 256: thread t owns 4 channels
-// (t % (D/4)) of row t / (D/4) of its block of RPB = 1024 / D rows.
+// Merges the key splits: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s per query row.
+// One wave per (sequence, KV head, 32-row block, 32-channel block); lanes map to the
+// partials exactly as the accumulator registers did, the result is transposed through LDS
+// so that the bf16 rows leave as 16-byte stores.
 template <int D>
-__global__ __launch_bounds__(256) void attn_combine_kernel(const AttnParams p) {
-    constexpr int TPR = D / 4;      // threads per row
-    constexpr int RPB = 256 / TPR;  // rows per block
+__global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p) {
+    constexpr int DB = D / 32;
     __shared__ int32_t sp[VS_MAX_TREE];
     __shared__ int32_t sflag;
+    __shared__ __attribute__((aligned(16))) uint16_t so[kRowBlock][32 + 8];
     const int unit = blockIdx.y;
     const int b = unit / p.Hkv, kvh = unit % p.Hkv;
+    const int rbk = blockIdx.x / DB, db = blockIdx.x % DB;
+    const int lane = threadIdx.x, col = lane & 31, half = lane >> 5;
     const int32_t tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
     const int32_t S = p.prefix_len[b];
     if (tree_code != VS_STATUS_OK || !prefix_ok(p, S)) return;
-    const int row = blockIdx.x * RPB + threadIdx.x / TPR;
-    const int ch = (threadIdx.x % TPR) * 4;
-    if (row >= p.rows) return;
     const int nk = S + p.T;
     const int nsplit = min(p.num_splits, (nk + p.keys_per_split - 1) / p.keys_per_split);
-    const int64_t base = (int64_t)unit * p.num_splits * p.rows_pad + row;
+    const int64_t blk0 = part_block(p, unit, 0, rbk);
+    const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
     float M = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p.part_ml[(base + (int64_t)s * p.rows_pad) * 2]);
+    for (int s = 0; s < nsplit; ++s)
+        M = fmaxf(M, p.part_ml[((blk0 + s * blk_stride) * kRowBlock + col) * 2]);
     float den = 0.f;
-    f32x4 num = {0.f, 0.f, 0.f, 0.f};
+    f32x4 num[4];
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) num[q4] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < nsplit; ++s) {
-        const int64_t pr = base + (int64_t)s * p.rows_pad;
-        const float ms = p.part_ml[pr * 2];
-        if (ms == -INFINITY) continue; // this split saw no visible key for the row
-        const float w = __builtin_amdgcn_exp2f(ms - M);
-        den += w * p.part_ml[pr * 2 + 1];
-        const f32x4 o = *(const f32x4*)(p.part_o + pr * D + ch);
-        num += w * o;
+        const int64_t blk = blk0 + s * blk_stride;
+        const f32x2 ml = *(const f32x2*)(p.part_ml + (blk * kRowBlock + col) * 2);
+        const float* po = p.part_o + blk * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
+        f32x4 o[4];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) o[q4] = __builtin_nontemporal_load((const f32x4*)(po + q4 * 256));
+        // a split that saw no visible key for the row has max -inf, sum 0 and zero partials
+        const float w = (ml[0] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[0] - M);
+        den += w * ml[1];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * o[q4];
     }
     const float inv = 1.f / den;
-    const int node = row / p.group;
-    const int hq = kvh * p.group + (row - node * p.group);
-    uint16_t* o = (uint16_t*)p.out + (((int64_t)b * p.T + node) * p.Hq + hq) * D + ch;
-    u32x2 w;
-    w[0] = pack_bf16x2(num[0] * inv, num[1] * inv);
-    w[1] = pack_bf16x2(num[2] * inv, num[3] * inv);
-    *(u32x2*)o = w;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+        u32x2 w;
+        w[0] = pack_bf16x2(num[q4][0] * inv, num[q4][1] * inv);
+        w[1] = pack_bf16x2(num[q4][2] * inv, num[q4][3] * inv);
+        *(u32x2*)&so[col][8 * q4 + 4 * half] = w;
+    }
+    __syncthreads();
+    uint16_t* out = (uint16_t*)p.out;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int rl = i * 16 + (lane >> 2), ch = lane & 3;
+        const int row = rbk * kRowBlock + rl;
+        if (row < p.rows) {
+            const int node = row / p.group;
+            const int hq = kvh * p.group + (row - node * p.group);
+            *(u32x4*)(out + (((int64_t)b * p.T + node) * p.Hq + hq) * D + db * 32 + ch * 8) = *(const u32x4*)&so[rl][ch * 8];
+        }
+    }
 }
 
 template <int D, int RPW>
@@ -339,10 +431,9 @@ hipError_t launch_attention_mfma(const AttnParams& p, int rpw, int waves, hipStr
 
 hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t s) {
     (void)dtype;
-    const int rpb = 1024 / p.d;
-    const dim3 grid((p.rows + rpb - 1) / rpb, p.B * p.Hkv);
-    if (p.d == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), grid, dim3(256), 0, s, p);
-    else if (p.d == 64) hipLaunchKernelGGL((attn_combine_kernel<64>), grid, dim3(256), 0, s, p);
+    const dim3 grid((p.rows_pad / kRowBlock) * (p.d / 32), p.B * p.Hkv);
+    if (p.d == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), grid, dim3(kWave), 0, s, p);
+    else if (p.d == 64) hipLaunchKernelGGL((attn_combine_kernel<64>), grid, dim3(kWave), 0, s, p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
