@@ -43,6 +43,9 @@ int32_t check_desc(const vs_attn_desc* d) {
     }
     const bool mfma = d->impl == VS_IMPL_MFMA || (d->impl == VS_IMPL_AUTO && d->dtype == VS_BF16);
     if (mfma) {
+        // token offsets inside one (sequence, KV head) slice are kept in 32 bits
+        const int64_t span = d->paged ? (int64_t)d->block_size * d->stride_tok : need * d->stride_tok;
+        if (span >= ((int64_t)1 << 30)) return VS_ERR_LAYOUT;
         // 16-byte vector loads of 8 bf16
         if (d->stride_head % 8 || d->stride_tok % 8 || (d->paged ? d->stride_block % 8 : d->stride_seq % 8))
             return VS_ERR_LAYOUT;
@@ -71,12 +74,12 @@ Plan make_plan(const vs_attn_desc* d) {
     pl.waves = 1;
     while (pl.waves < need && pl.waves < kMaxWaves) pl.waves *= 2;
     pl.row_groups = (need + pl.waves - 1) / pl.waves;
-    const int tiles = ((int64_t)d->max_prefix_len + d->T + kTileKeys - 1) / kTileKeys;
+    const int tiles = ((int64_t)d->max_prefix_len + d->T + kIterKeys - 1) / kIterKeys;
     const int units = d->B * d->Hkv * pl.row_groups;
     int splits = d->num_splits;
     if (splits <= 0) {
         // enough workgroups to cover the 256 CUs (small workgroups: several per CU), but
-        // never fewer than two key tiles per split
+        // never fewer than two loop iterations per split
         const int target = 256 * (pl.waves >= 4 ? 1 : 4 / pl.waves);
         splits = (target + units - 1) / units;
         const int max_splits = (tiles + 1) / 2;
@@ -85,7 +88,7 @@ Plan make_plan(const vs_attn_desc* d) {
     if (splits < 1) splits = 1;
     if (splits > tiles) splits = tiles;
     const int tiles_per_split = (tiles + splits - 1) / splits;
-    pl.keys_per_split = tiles_per_split * kTileKeys;
+    pl.keys_per_split = tiles_per_split * kIterKeys;
     pl.num_splits = (tiles + tiles_per_split - 1) / tiles_per_split;
     pl.total_wgs = units * pl.num_splits;
     return pl;

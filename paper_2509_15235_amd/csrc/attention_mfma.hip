@@ -42,6 +42,8 @@ typedef __attribute__((address_space(3))) void lds_void;
 // nothing else (expcnt = 7, lgkmcnt = 15 are their maxima).
 constexpr int kWaitVm0 = 0x0F70;
 
+constexpr float kLazy = 8.f; // log2 slack of the running softmax reference
+
 // max / sum over the two 32-lane halves, result in every lane (v_permlane32_swap)
 __device__ __forceinline__ float half_max(float x) {
     const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -63,23 +65,29 @@ template <int D, int RPW, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) {
     constexpr int KS = D / 16;               // k-steps of the S^T product
     constexpr int DB = D / 32;               // 32-channel blocks of the output
-    constexpr int TILE = kTileKeys * D;      // elements per K (or V) tile
-    constexpr int IPT = TILE * 2 / 1024;     // 1 KB direct-to-LDS load instructions per tile
+    constexpr int SUB = kTileKeys * D;       // elements per 32-key block of K (or V)
+    constexpr int NSUB = kIterKeys / kTileKeys;
+    constexpr int TILE = NSUB * SUB;         // elements staged per iteration for K (or V)
+    constexpr int BPS = SUB * 2 / 1024;      // 1 KB direct-to-LDS load blocks per 32 keys
+    constexpr int IPT = NSUB * BPS;          // ... per iteration
     constexpr int IPW = (IPT + NW - 1) / NW; // ... issued by each wave
     // Two row blocks per wave at two waves per SIMD (256 registers each) do not leave room
     // for both blocks' queries next to the accumulators: the second block's query
     // fragments then live in a lane-private LDS slot (written once, by a direct load)
     // instead of being spilled to scratch memory by the compiler.
     constexpr bool QL = (RPW == 2 && NW == 8);
+    constexpr int QR0 = QL ? KS - 2 : KS;          // k-steps of row block 0 whose queries stay in registers
+    constexpr int NQL = QL ? (KS - QR0) + KS : 0;  // LDS query slots (1 KB each) per wave
+    constexpr int NBUF = 2;
 
     // Tiles live in LDS in 16-byte chunks placed so that every access is conflict-free and
     // every address is "per-lane constant + immediate". A direct-to-LDS load instruction
     // writes lane q's 16 bytes at (1 KB block i) + 16 q, and each lane may fetch any chunk:
-    //   K: block i, lane q holds row 16*(i / (D/32)) + q%16, chunk (D/32 == 4 ? 4*(i%4) : 4*(i%2)) + q/16
+    //   K: block i, lane q holds row 16*(i / (D/32)) + q%16, chunk 4*(i % (D/32)) + q/16
     //   V: block i, lane q holds row 16*(i / (D/32)) + 4*(q/16) + (q%16)/4, chunk 4*(i % (D/32)) + q%4
-    __shared__ __attribute__((aligned(1024))) uint16_t sK[2][TILE];
-    __shared__ __attribute__((aligned(1024))) uint16_t sV[2][TILE];
-    __shared__ __attribute__((aligned(1024))) uint16_t sQ[QL ? NW * KS * 512 : 8];
+    __shared__ __attribute__((aligned(1024))) uint16_t sK[NBUF][TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t sV[NBUF][TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t sQ[QL ? NW * NQL * 512 : 8];
     __shared__ int32_t sp[VS_MAX_TREE];
     __shared__ int32_t sflag;
 
@@ -123,12 +131,12 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     const int stride_tok = (int)p.stride_tok;           // host guarantees 32-bit lane offsets
     const int krow_l = lane & 15, kcol_l = (lane >> 4) * 8;
     const int vrow_l = 4 * (lane >> 4) + ((lane & 15) >> 2), vcol_l = (lane & 3) * 8;
-    auto fetch = [&](int kt, int buf) {
+    auto fetch = [&](int kt, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < IPW; ++j) {
             const int i = wave * IPW + j; // block index, uniform per wave
             if (i < IPT) {
-                const int r0 = kt + 16 * (i / DB);
+                const int r0 = kt + kTileKeys * (i / BPS) + 16 * ((i % BPS) / DB);
                 const int c0 = 32 * (i % DB);
                 int ktok = min(r0 + krow_l, k1 - 1), vtok = min(r0 + vrow_l, k1 - 1);
                 int64_t base = head_base;
@@ -165,10 +173,12 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
         if (wave_active) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                if (QL && rb == 1)
-                    __builtin_amdgcn_global_load_lds(qr + ks * 16, (lds_void*)(sQ + (wave * KS + ks) * 512), 16, 0, 0);
-                else
+                if (QL && (rb == 1 || ks >= QR0)) {
+                    const int slot = rb == 1 ? (KS - QR0) + ks : ks - QR0;
+                    __builtin_amdgcn_global_load_lds(qr + ks * 16, (lds_void*)(sQ + (wave * NQL + slot) * 512), 16, 0, 0);
+                } else {
                     qf[rb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qr + ks * 16));
+                }
             }
         }
     }
@@ -190,14 +200,15 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     const int t16 = lane & 15;                                               // transposing V read: 16-lane groups
     const int v_lane = half * 128 + (t16 >> 2) * 32 + ((lane >> 4) & 1) * 16 + ((t16 >> 1) & 1) * 8 + (t16 & 1) * 4;
     //                 + sl*(DB*512) + db*512 + u*256
-    const uint16_t* q_lane = sQ + wave * (KS * 512) + lane * 8;              // + ks*512
+    const uint16_t* q_lane = sQ + wave * (NQL * 512) + lane * 8;             // + slot*512
 
-    // One 32-key tile for this wave's row blocks. MASKED tiles hold tree slots or the end
-    // of the key range; all others are pure prefix and skip the visibility logic.
-    auto tile = [&](auto masked_tag, int kt, int buf) {
+    // Stage 1 of a 32-key tile for this wave's row blocks: scores, mask, online softmax,
+    // probabilities as MFMA operands in pf. MASKED tiles hold tree slots or the end of the
+    // key range; all others are pure prefix and skip the visibility logic.
+    bf16x8 pf[RPW][2];
+    auto score = [&](auto masked_tag, int kt, const uint16_t* kblock) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const uint16_t* tK = sK[buf] + k_lane;
-        const uint16_t* tV = sV[buf] + v_lane;
+        const uint16_t* tK = kblock + k_lane;
         // ---- per row block: S^T = K . Q^T, mask, online softmax, P as a B operand.
         // Lane (col, half) holds keys 8*(r/4) + 4*half + r%4 of row `col`.
         // Each K fragment is read from LDS once and feeds every row block.
@@ -211,12 +222,13 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
             const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(tK + ks * 256));
 #pragma unroll
             for (int rb = 0; rb < RPW; ++rb) {
-                const bf16x8 bq = (QL && rb == 1) ? __builtin_bit_cast(bf16x8, *(const u32x4*)(q_lane + ks * 512))
-                                                  : qf[rb][ks];
+                const int slot = rb == 1 ? (KS - QR0) + ks : ks - QR0;
+                const bf16x8 bq = (QL && (rb == 1 || ks >= QR0))
+                                      ? __builtin_bit_cast(bf16x8, *(const u32x4*)(q_lane + slot * 512))
+                                      : qf[rb][ks];
                 sc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq, sc[rb], 0, 0, 0);
             }
         }
-        bf16x8 pf[RPW][2];
 #pragma unroll
         for (int rb = 0; rb < RPW; ++rb) {
             f32x16& s = sc[rb];
@@ -236,7 +248,12 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
             for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
             mx = fmaxf(mx, s[15]);
             mx = half_max(mx);
-            const float m_new = fmaxf(m2[rb], mx * p.scale_log2);
+            // Lazy reference maximum: m2 only moves when the tile's maximum exceeds it by more
+            // than kLazy (2^8 in the linear domain). Probabilities then reach at most 2^8,
+            // well inside bf16/fp32 range, the result is unchanged (numerator and denominator
+            // share the reference), and the accumulator rescale below becomes rare.
+            const float mt = mx * p.scale_log2;
+            const float m_new = (mt > m2[rb] + kLazy) ? mt : m2[rb];
             const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new; // no visible key yet
             const float alpha = __builtin_amdgcn_exp2f(m2[rb] - m_use);
             m2[rb] = m_new;
@@ -265,8 +282,11 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
             }
         }
 
-        // ---- O^T += V^T . P^T. The A operand (channel `col` of block db, keys in the
-        // order P holds them) comes from two transposing reads of 4 keys x 16 channels.
+    };
+    // Stage 2: O^T += V^T . P^T. The A operand (channel `col` of block db, keys in the
+    // order P holds them) comes from two transposing reads of 4 keys x 16 channels.
+    auto pv = [&](const uint16_t* vblock) __attribute__((always_inline)) {
+        const uint16_t* tV = vblock + v_lane;
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl) {
 #pragma unroll
@@ -285,23 +305,31 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __syncthreads();
 
-    // Tiles that end at or before min(S, k1) are pure prefix; the rest need the mask.
-    const int k_plain = k0 + max(0, (min(S, k1) - k0) / kTileKeys) * kTileKeys;
+    // Iterations whose 64 keys end at or before min(S, k1) are pure prefix; the rest take
+    // the masked path for both of their 32-key blocks.
+    const int k_plain = k0 + max(0, (min(S, k1) - k0) / kIterKeys) * kIterKeys;
     int buf = 0;
     int kt = k0;
-    for (; kt < k_plain; kt += kTileKeys, buf ^= 1) {
-        // the other buffer's last readers passed the barrier that ended the previous iteration
-        if (kt + kTileKeys < k1) fetch(kt + kTileKeys, buf ^ 1);
-        if (wave_active) tile(std::false_type{}, kt, buf);
-        __builtin_amdgcn_s_waitcnt(kWaitVm0); // the next tile has landed in LDS ...
-        __syncthreads();                      // ... and everyone is done with this one
-    }
-    for (; kt < k1; kt += kTileKeys, buf ^= 1) {
-        if (kt + kTileKeys < k1) fetch(kt + kTileKeys, buf ^ 1);
-        if (wave_active) tile(std::true_type{}, kt, buf);
+    // One iteration: start the next 64 keys' copy into the other buffer (its readers all
+    // passed the previous barrier), work through this buffer, then wait until the copy
+    // has landed and every wave is done.
+    auto step = [&](auto masked_tag) __attribute__((always_inline)) {
+        if (kt + kIterKeys < k1) fetch(kt + kIterKeys, buf ^ 1);
+        if (wave_active) {
+#pragma unroll
+            for (int sub = 0; sub < NSUB; ++sub) {
+                if (sub == 0 || kt + sub * kTileKeys < k1) {
+                    score(masked_tag, kt + sub * kTileKeys, sK[buf] + sub * SUB);
+                    pv(sV[buf] + sub * SUB);
+                }
+            }
+        }
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();
-    }
+        buf ^= 1;
+    };
+    for (; kt < k_plain; kt += kIterKeys) step(std::false_type{});
+    for (; kt < k1; kt += kIterKeys) step(std::true_type{});
 
     if (!wave_active) return;
 
@@ -335,7 +363,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const f32x4 w = {acc[rb][db][4 * q4], acc[rb][db][4 * q4 + 1], acc[rb][db][4 * q4 + 2],
                                      acc[rb][db][4 * q4 + 3]};
-                    __builtin_nontemporal_store(w, (f32x4*)(po + (db * 4 + q4) * 256));
+                    *(f32x4*)(po + (db * 4 + q4) * 256) = w;
                 }
             if (half == 0) {
                 const f32x2 ml = {m2[rb], l};
@@ -366,6 +394,7 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
     const int nsplit = min(p.num_splits, (nk + p.keys_per_split - 1) / p.keys_per_split);
     const int64_t blk0 = part_block(p, unit, 0, rbk);
     const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
+    // (max, sum) of every split for this lane's row: independent loads, issued together
     float M = -INFINITY;
     for (int s = 0; s < nsplit; ++s)
         M = fmaxf(M, p.part_ml[((blk0 + s * blk_stride) * kRowBlock + col) * 2]);
@@ -373,18 +402,27 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
     f32x4 num[4];
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) num[q4] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < nsplit; ++s) {
-        const int64_t blk = blk0 + s * blk_stride;
-        const f32x2 ml = *(const f32x2*)(p.part_ml + (blk * kRowBlock + col) * 2);
-        const float* po = p.part_o + blk * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
-        f32x4 o[4];
+    for (int s0 = 0; s0 < nsplit; s0 += 4) {
+        f32x2 ml[4];
+        f32x4 o[4][4];
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) o[q4] = __builtin_nontemporal_load((const f32x4*)(po + q4 * 256));
-        // a split that saw no visible key for the row has max -inf, sum 0 and zero partials
-        const float w = (ml[0] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[0] - M);
-        den += w * ml[1];
+        for (int u = 0; u < 4; ++u) {
+            const int s = min(s0 + u, nsplit - 1); // past the end: re-read the last split, weight 0
+            const int64_t blk = blk0 + s * blk_stride;
+            ml[u] = *(const f32x2*)(p.part_ml + (blk * kRowBlock + col) * 2);
+            const float* po = p.part_o + blk * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * o[q4];
+            for (int q4 = 0; q4 < 4; ++q4) o[u][q4] = *(const f32x4*)(po + q4 * 256);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            // a split that saw no visible key for the row has max -inf, sum 0 and zero partials
+            const bool live = (s0 + u < nsplit) && (ml[u][0] != -INFINITY);
+            const float w = live ? __builtin_amdgcn_exp2f(ml[u][0] - M) : 0.f;
+            den += w * ml[u][1];
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * o[u][q4];
+        }
     }
     const float inv = 1.f / den;
 #pragma unroll

@@ -9,7 +9,8 @@
 namespace vs {
 
 constexpr int kWave = 64;
-constexpr int kTileKeys = 32;   // keys per LDS tile of the MFMA attention kernel
+constexpr int kTileKeys = 32;   // keys per MFMA score block of the attention kernel
+constexpr int kIterKeys = 64;   // keys staged in LDS per loop iteration (two score blocks)
 constexpr int kRowBlock = 32;   // query rows per MFMA row block
 constexpr int kMaxWaves = 8;    // waves per workgroup in the MFMA attention kernel
 constexpr int kArgmaxBlock = 256;
@@ -37,7 +38,7 @@ struct AttnParams {
     float scale;                // softmax scale
     float scale_log2;           // softmax scale * log2(e)
     int32_t num_splits;         // grid extent over key splits
-    int32_t keys_per_split;     // multiple of kTileKeys
+    int32_t keys_per_split;     // multiple of kIterKeys
     int32_t row_groups;
     int32_t rows_per_group;     // waves_per_group * row blocks per wave * kRowBlock
     int32_t total_wgs;          // B * Hkv * num_splits * row_groups
