@@ -87,6 +87,7 @@ Plan make_plan(const vs_attn_desc* d) {
     }
     if (splits < 1) splits = 1;
     if (splits > tiles) splits = tiles;
+    if (splits > 64) splits = 64; // the combine kernel stages at most 64 splits
     const int tiles_per_split = (tiles + splits - 1) / splits;
     pl.keys_per_split = tiles_per_split * kIterKeys;
     pl.num_splits = (tiles + tiles_per_split - 1) / tiles_per_split;

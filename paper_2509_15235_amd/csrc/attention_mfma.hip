@@ -60,13 +60,24 @@ __device__ __forceinline__ float half_sum(float x) {
 __device__ __forceinline__ int64_t part_block(const AttnParams& p, int64_t unit, int split, int rbk) {
     return (unit * p.num_splits + split) * (int64_t)(p.rows_pad / kRowBlock) + rbk;
 }
+// (max, sum) pairs are grouped per row block with the splits adjacent: index of the
+// first of the 32 rows of (unit, rbk, split), in pairs.
+__device__ __forceinline__ int64_t ml_block(const AttnParams& p, int64_t unit, int split, int rbk) {
+    return ((unit * (p.rows_pad / kRowBlock) + rbk) * p.num_splits + split) * (int64_t)kRowBlock;
+}
 
 template <int D, int RPW, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) {
     constexpr int KS = D / 16;               // k-steps of the S^T product
     constexpr int DB = D / 32;               // 32-channel blocks of the output
+    // Two waves per SIMD (NW == 8) share one barrier per iteration and would otherwise sit
+    // in the same stage all the time: both on the matrix core, then both on the VALU. The
+    // upper half of the waves therefore runs its P.V stage one iteration late (STAGGER),
+    // which needs 32-key iterations and a third LDS buffer.
+    constexpr bool STAGGER = (NW == 8);
     constexpr int SUB = kTileKeys * D;       // elements per 32-key block of K (or V)
-    constexpr int NSUB = kIterKeys / kTileKeys;
+    constexpr int NSUB = STAGGER ? 1 : kIterKeys / kTileKeys;
+    constexpr int ITER = NSUB * kTileKeys;   // keys per loop iteration
     constexpr int TILE = NSUB * SUB;         // elements staged per iteration for K (or V)
     constexpr int BPS = SUB * 2 / 1024;      // 1 KB direct-to-LDS load blocks per 32 keys
     constexpr int IPT = NSUB * BPS;          // ... per iteration
@@ -76,9 +87,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     // fragments then live in a lane-private LDS slot (written once, by a direct load)
     // instead of being spilled to scratch memory by the compiler.
     constexpr bool QL = (RPW == 2 && NW == 8);
-    constexpr int QR0 = QL ? KS - 2 : KS;          // k-steps of row block 0 whose queries stay in registers
+    constexpr int QR0 = QL ? KS / 2 : KS;          // k-steps of row block 0 whose queries stay in registers
     constexpr int NQL = QL ? (KS - QR0) + KS : 0;  // LDS query slots (1 KB each) per wave
-    constexpr int NBUF = 2;
+    constexpr int NBUF = STAGGER ? 3 : 2;
 
     // Tiles live in LDS in 16-byte chunks placed so that every access is conflict-free and
     // every address is "per-lane constant + immediate". A direct-to-LDS load instruction
@@ -110,7 +121,15 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     const int kvh = rest % p.Hkv;
     const int b = rest / p.Hkv;
 
-    const int32_t tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
+    // With caller-supplied masks the tree was checked by the mask builder (which zeroes the
+    // masks of a malformed tree); otherwise check it here.
+    int32_t tree_code = VS_STATUS_OK;
+    if (p.tree_mask) {
+        if (tid == 0) sflag = 0;
+        __syncthreads();
+    } else {
+        tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
+    }
     const int32_t S = p.prefix_len[b];
     const bool s_ok = prefix_ok(p, S);
     if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
@@ -211,23 +230,40 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
         const uint16_t* tK = kblock + k_lane;
         // ---- per row block: S^T = K . Q^T, mask, online softmax, P as a B operand.
         // Lane (col, half) holds keys 8*(r/4) + 4*half + r%4 of row `col`.
-        // Each K fragment is read from LDS once and feeds every row block.
+        // Each K fragment is read from LDS once and feeds every row block. The reads run
+        // PF k-steps ahead of the MFMAs that consume them (software pipeline; the
+        // scheduling barriers keep the compiler from serialising read -> wait -> MFMA).
+        constexpr int PF = 2;
         f32x16 sc[RPW];
 #pragma unroll
         for (int rb = 0; rb < RPW; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sc[rb][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(tK + ks * 256));
+        u32x4 ka[PF + 1], qa[PF + 1][RPW]; // fragment ring buffers (only LDS-resident queries use qa)
+        auto load_frags = [&](int ks) __attribute__((always_inline)) {
+            ka[ks % (PF + 1)] = *(const u32x4*)(tK + ks * 256);
 #pragma unroll
             for (int rb = 0; rb < RPW; ++rb) {
-                const int slot = rb == 1 ? (KS - QR0) + ks : ks - QR0;
-                const bf16x8 bq = (QL && (rb == 1 || ks >= QR0))
-                                      ? __builtin_bit_cast(bf16x8, *(const u32x4*)(q_lane + slot * 512))
-                                      : qf[rb][ks];
+                if (QL && (rb == 1 || ks >= QR0)) {
+                    const int slot = rb == 1 ? (KS - QR0) + ks : ks - QR0;
+                    qa[ks % (PF + 1)][rb] = *(const u32x4*)(q_lane + slot * 512);
+                }
+            }
+        };
+#pragma unroll
+        for (int ks = 0; ks < PF; ++ks) load_frags(ks);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + PF < KS) load_frags(ks + PF);
+            __builtin_amdgcn_sched_barrier(0);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, ka[ks % (PF + 1)]);
+#pragma unroll
+            for (int rb = 0; rb < RPW; ++rb) {
+                const bf16x8 bq = (QL && (rb == 1 || ks >= QR0)) ? __builtin_bit_cast(bf16x8, qa[ks % (PF + 1)][rb])
+                                                                  : qf[rb][ks];
                 sc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq, sc[rb], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int rb = 0; rb < RPW; ++rb) {
@@ -287,49 +323,72 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     // order P holds them) comes from two transposing reads of 4 keys x 16 channels.
     auto pv = [&](const uint16_t* vblock) __attribute__((always_inline)) {
         const uint16_t* tV = vblock + v_lane;
+        constexpr int NV = 2 * DB; // V^T fragments per 32 keys, step = sl * DB + db
+        constexpr int PF = 2;
+        s16x4 va[PF + 1][2];
+        auto load_v = [&](int st) __attribute__((always_inline)) {
+            const int sl = st / DB, db = st % DB;
+            va[st % (PF + 1)][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tV + sl * (DB * 512) + db * 512));
+            va[st % (PF + 1)][1] =
+                __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tV + sl * (DB * 512) + db * 512 + 256));
+        };
 #pragma unroll
-        for (int sl = 0; sl < 2; ++sl) {
+        for (int st = 0; st < PF; ++st) load_v(st);
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tV + sl * (DB * 512) + db * 512));
-                const s16x4 hi =
-                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tV + sl * (DB * 512) + db * 512 + 256));
-                const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        for (int st = 0; st < NV; ++st) {
+            if (st + PF < NV) load_v(st + PF);
+            __builtin_amdgcn_sched_barrier(0);
+            const int sl = st / DB, db = st % DB;
+            const bf16x8 a = __builtin_bit_cast(
+                bf16x8, __builtin_shufflevector(va[st % (PF + 1)][0], va[st % (PF + 1)][1], 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
-                for (int rb = 0; rb < RPW; ++rb)
-                    acc[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[rb][sl], acc[rb][db], 0, 0, 0);
-            }
+            for (int rb = 0; rb < RPW; ++rb)
+                acc[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[rb][sl], acc[rb][db], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __syncthreads();
 
-    // Iterations whose 64 keys end at or before min(S, k1) are pure prefix; the rest take
-    // the masked path for both of their 32-key blocks.
-    const int k_plain = k0 + max(0, (min(S, k1) - k0) / kIterKeys) * kIterKeys;
-    int buf = 0;
+    // Iterations whose keys end at or before min(S, k1) are pure prefix; the rest take the
+    // masked path.
+    const int k_plain = k0 + max(0, (min(S, k1) - k0) / ITER) * ITER;
+    int buf = 0, prv = 0;
     int kt = k0;
-    // One iteration: start the next 64 keys' copy into the other buffer (its readers all
-    // passed the previous barrier), work through this buffer, then wait until the copy
-    // has landed and every wave is done.
-    auto step = [&](auto masked_tag) __attribute__((always_inline)) {
-        if (kt + kIterKeys < k1) fetch(kt + kIterKeys, buf ^ 1);
+    // One iteration: start the next keys' copy into a buffer nobody reads any more, do this
+    // wave's stages, then wait until the copy has landed and every wave is done.
+    auto step = [&](auto late_tag, auto masked_tag) __attribute__((always_inline)) {
+        constexpr bool LATE = decltype(late_tag)::value;
+        const int nxt = (buf + 1 == NBUF) ? 0 : buf + 1;
+        if (kt + ITER < k1) fetch(kt + ITER, nxt);
         if (wave_active) {
+            if constexpr (LATE) {
+                if (kt > k0) pv(sV[prv]); // previous iteration's probabilities, kept in pf
+                score(masked_tag, kt, sK[buf]);
+            } else {
 #pragma unroll
-            for (int sub = 0; sub < NSUB; ++sub) {
-                if (sub == 0 || kt + sub * kTileKeys < k1) {
-                    score(masked_tag, kt + sub * kTileKeys, sK[buf] + sub * SUB);
-                    pv(sV[buf] + sub * SUB);
+                for (int sub = 0; sub < NSUB; ++sub) {
+                    if (sub == 0 || kt + sub * kTileKeys < k1) {
+                        score(masked_tag, kt + sub * kTileKeys, sK[buf] + sub * SUB);
+                        pv(sV[buf] + sub * SUB);
+                    }
                 }
             }
         }
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();
-        buf ^= 1;
+        prv = buf;
+        buf = nxt;
     };
-    for (; kt < k_plain; kt += kIterKeys) step(std::false_type{});
-    for (; kt < k1; kt += kIterKeys) step(std::true_type{});
+    if (STAGGER && wave >= NW / 2) {
+        for (; kt < k_plain; kt += ITER) step(std::true_type{}, std::false_type{});
+        for (; kt < k1; kt += ITER) step(std::true_type{}, std::true_type{});
+        if (wave_active) pv(sV[prv]);
+    } else {
+        for (; kt < k_plain; kt += ITER) step(std::false_type{}, std::false_type{});
+        for (; kt < k1; kt += ITER) step(std::false_type{}, std::true_type{});
+    }
 
     if (!wave_active) return;
 
@@ -367,7 +426,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
                 }
             if (half == 0) {
                 const f32x2 ml = {m2[rb], l};
-                *(f32x2*)(p.part_ml + (blk * kRowBlock + col) * 2) = ml;
+                const int64_t mlb = ml_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
+                *(f32x2*)(p.part_ml + (mlb + col) * 2) = ml;
             }
         }
     }
@@ -376,50 +436,52 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
 // Merges the key splits: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s per query row.
 // One wave per (sequence, KV head, 32-row block, 32-channel block); lanes map to the
 // partials exactly as the accumulator registers did, the result is transposed through LDS
-// so that the bf16 rows leave as 16-byte stores.
+// so that the bf16 rows leave as 16-byte stores. A sequence whose prefix length is out of
+// range is skipped; a malformed tree (reported by the main kernel) leaves unspecified output.
+constexpr int kCombineMaxSplits = 64; // (max, sum) pairs staged in LDS: 64 splits x 32 rows
 template <int D>
 __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p) {
     constexpr int DB = D / 32;
-    __shared__ int32_t sp[VS_MAX_TREE];
-    __shared__ int32_t sflag;
+    __shared__ f32x2 sml[kCombineMaxSplits * kRowBlock];
     __shared__ __attribute__((aligned(16))) uint16_t so[kRowBlock][32 + 8];
     const int unit = blockIdx.y;
     const int b = unit / p.Hkv, kvh = unit % p.Hkv;
     const int rbk = blockIdx.x / DB, db = blockIdx.x % DB;
     const int lane = threadIdx.x, col = lane & 31, half = lane >> 5;
-    const int32_t tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
     const int32_t S = p.prefix_len[b];
-    if (tree_code != VS_STATUS_OK || !prefix_ok(p, S)) return;
+    if (!prefix_ok(p, S)) return;
     const int nk = S + p.T;
     const int nsplit = min(p.num_splits, (nk + p.keys_per_split - 1) / p.keys_per_split);
-    const int64_t blk0 = part_block(p, unit, 0, rbk);
-    const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
-    // (max, sum) of every split for this lane's row: independent loads, issued together
+
+    // stage every split's (max, sum) of the 32 rows: contiguous in the workspace
+    const f32x2* gml = (const f32x2*)p.part_ml + ml_block(p, unit, 0, rbk);
+    for (int i = lane; i < nsplit * kRowBlock; i += kWave) sml[i] = gml[i];
+    __syncthreads();
     float M = -INFINITY;
-    for (int s = 0; s < nsplit; ++s)
-        M = fmaxf(M, p.part_ml[((blk0 + s * blk_stride) * kRowBlock + col) * 2]);
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, sml[s * kRowBlock + col][0]);
+
     float den = 0.f;
     f32x4 num[4];
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) num[q4] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int64_t blk0 = part_block(p, unit, 0, rbk);
+    const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
     for (int s0 = 0; s0 < nsplit; s0 += 4) {
-        f32x2 ml[4];
         f32x4 o[4][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int s = min(s0 + u, nsplit - 1); // past the end: re-read the last split, weight 0
-            const int64_t blk = blk0 + s * blk_stride;
-            ml[u] = *(const f32x2*)(p.part_ml + (blk * kRowBlock + col) * 2);
-            const float* po = p.part_o + blk * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
+            const float* po = p.part_o + (blk0 + s * blk_stride) * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) o[u][q4] = *(const f32x4*)(po + q4 * 256);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            const f32x2 ml = sml[min(s0 + u, nsplit - 1) * kRowBlock + col];
             // a split that saw no visible key for the row has max -inf, sum 0 and zero partials
-            const bool live = (s0 + u < nsplit) && (ml[u][0] != -INFINITY);
-            const float w = live ? __builtin_amdgcn_exp2f(ml[u][0] - M) : 0.f;
-            den += w * ml[u][1];
+            const bool live = (s0 + u < nsplit) && (ml[0] != -INFINITY);
+            const float w = live ? __builtin_amdgcn_exp2f(ml[0] - M) : 0.f;
+            den += w * ml[1];
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * o[u][q4];
         }
