@@ -126,6 +126,8 @@ typedef struct vs_attn_desc {
     const int32_t* block_table; /* paged: device [B, max_blocks] */
     int32_t impl;           /* vs_attn_impl */
     int32_t num_splits;     /* key splits per (sequence, KV head); 0 = choose */
+    int32_t rows_per_wave;  /* MFMA path: 32-row blocks per wave, 1 or 2; 0 = choose */
+    int32_t waves_per_group; /* MFMA path: waves per workgroup, 1, 2, 4 or 8; 0 = choose */
 } vs_attn_desc;
 
 /* What a call with this descriptor would launch (for tests and reports). */
@@ -135,6 +137,7 @@ typedef struct vs_attn_plan {
     int32_t keys_per_split;
     int32_t row_groups;      /* workgroups that share one (sequence, KV head, split) */
     int32_t waves_per_group;
+    int32_t rows_per_wave;   /* 32-row blocks per wave (MFMA path) */
     int32_t workgroups;      /* main kernel grid size */
     int32_t combine;         /* 1 if a split-combine kernel follows */
 } vs_attn_plan;

@@ -31,14 +31,15 @@ class AttnDesc(ctypes.Structure):
         ("max_blocks", ctypes.c_int32), ("num_blocks", ctypes.c_int32), ("capacity", ctypes.c_int64),
         ("stride_seq", ctypes.c_int64), ("stride_block", ctypes.c_int64), ("stride_head", ctypes.c_int64),
         ("stride_tok", ctypes.c_int64), ("block_table", ctypes.c_void_p), ("impl", ctypes.c_int32),
-        ("num_splits", ctypes.c_int32),
+        ("num_splits", ctypes.c_int32), ("rows_per_wave", ctypes.c_int32), ("waves_per_group", ctypes.c_int32),
     ]
 
 
 class AttnPlan(ctypes.Structure):
     _fields_ = [
         ("impl", ctypes.c_int32), ("num_splits", ctypes.c_int32), ("keys_per_split", ctypes.c_int32),
-        ("row_groups", ctypes.c_int32), ("waves_per_group", ctypes.c_int32), ("workgroups", ctypes.c_int32),
+        ("row_groups", ctypes.c_int32), ("waves_per_group", ctypes.c_int32), ("rows_per_wave", ctypes.c_int32),
+        ("workgroups", ctypes.c_int32),
         ("combine", ctypes.c_int32),
     ]
 

@@ -11,6 +11,8 @@ namespace vs {
 
 namespace {
 
+constexpr int kVecPerThread = 4; // 16-byte loads per thread and chunk
+
 struct Best {
     float v;
     int32_t i;
@@ -46,28 +48,23 @@ __global__ __launch_bounds__(kArgmaxBlock) void argmax_partial_kernel(const Acce
     const int end = min(p.V, begin + p.chunk_elems);
     Best best = {-INFINITY, INT32_MAX};
     if (p.vec_ok) {
+        // chunk_elems = 4 * kArgmaxBlock * kVecPerThread: every thread's loads are issued
+        // before the first compare, ascending index order per thread keeps "first maximum"
         const int nvec = (end - begin) >> 2;
         const f32x4* __restrict__ lv = (const f32x4*)(lg + begin);
-        int k = threadIdx.x;
-        // four independent 16-byte loads in flight per thread
-        for (; k + 3 * kArgmaxBlock < nvec; k += 4 * kArgmaxBlock) {
-            const f32x4 a0 = __builtin_nontemporal_load(lv + k);
-            const f32x4 a1 = __builtin_nontemporal_load(lv + k + kArgmaxBlock);
-            const f32x4 a2 = __builtin_nontemporal_load(lv + k + 2 * kArgmaxBlock);
-            const f32x4 a3 = __builtin_nontemporal_load(lv + k + 3 * kArgmaxBlock);
+        f32x4 a[kVecPerThread];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) take(best, a0[e], begin + 4 * k + e);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) take(best, a1[e], begin + 4 * (k + kArgmaxBlock) + e);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) take(best, a2[e], begin + 4 * (k + 2 * kArgmaxBlock) + e);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) take(best, a3[e], begin + 4 * (k + 3 * kArgmaxBlock) + e);
+        for (int j = 0; j < kVecPerThread; ++j) {
+            const int k = threadIdx.x + j * kArgmaxBlock;
+            a[j] = (k < nvec) ? __builtin_nontemporal_load(lv + k) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         }
-        for (; k < nvec; k += kArgmaxBlock) {
-            const f32x4 a = __builtin_nontemporal_load(lv + k);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) take(best, a[e], begin + 4 * k + e);
+        for (int j = 0; j < kVecPerThread; ++j) {
+            const int k = threadIdx.x + j * kArgmaxBlock;
+            if (k < nvec) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) take(best, a[j][e], begin + 4 * k + e);
+            }
         }
         for (int t = begin + 4 * nvec + threadIdx.x; t < end; t += kArgmaxBlock) take(best, lg[t], t);
     } else {
@@ -100,14 +97,26 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
     const int T = p.T;
     const int32_t tree_code = load_tree(p.parent + (int64_t)b * T, T, sp, &sflag);
 
-    for (int i = wave; i < T; i += 4) {
-        const int64_t row = (int64_t)b * T + i;
+    // four threads per row share the row's chunk results (T <= 64 rows, 256 threads)
+    {
+        const int i = tid >> 2, sub = tid & 3;
         Best best = {-INFINITY, INT32_MAX};
-        for (int c = lane; c < p.chunks; c += kWave) take(best, p.part_val[row * p.chunks + c], p.part_idx[row * p.chunks + c]);
-        best = wave_best(best);
-        if (lane == 0) {
+        if (i < T) {
+            const int64_t row = (int64_t)b * T + i;
+            const float* pv = p.part_val + row * p.chunks;
+            const int32_t* pi = p.part_idx + row * p.chunks;
+            for (int c = sub; c < p.chunks; c += 4) take(best, pv[c], pi[c]);
+        }
+#pragma unroll
+        for (int o = 1; o <= 2; o <<= 1) {
+            const float ov = __shfl_xor(best.v, o);
+            const int32_t oi = __shfl_xor(best.i, o);
+            take(best, ov, oi);
+        }
+        if (i < T && sub == 0) {
             // what a left-to-right '>' scan returns: a NaN in column 0 is never displaced,
             // and a row with nothing above -inf keeps index 0
+            const int64_t row = (int64_t)b * T + i;
             const float first = p.logits[row * p.ld];
             int32_t idx = best.i;
             if (first != first || idx == INT32_MAX) idx = 0;

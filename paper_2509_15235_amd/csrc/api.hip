@@ -29,7 +29,10 @@ int32_t check_desc(const vs_attn_desc* d) {
     if (d->dtype != VS_BF16 && d->dtype != VS_F32) return VS_ERR_DTYPE;
     if (d->impl != VS_IMPL_AUTO && d->impl != VS_IMPL_GENERIC && d->impl != VS_IMPL_MFMA) return VS_ERR_SHAPE;
     if (d->impl == VS_IMPL_MFMA && d->dtype != VS_BF16) return VS_ERR_DTYPE;
-    if (d->num_splits < 0) return VS_ERR_SHAPE;
+    if (d->num_splits < 0 || d->rows_per_wave < 0 || d->rows_per_wave > 2) return VS_ERR_SHAPE;
+    if (d->waves_per_group != 0 && d->waves_per_group != 1 && d->waves_per_group != 2 && d->waves_per_group != 4 &&
+        d->waves_per_group != 8)
+        return VS_ERR_SHAPE;
     if (d->stride_head < 0 || d->stride_tok < d->d) return VS_ERR_LAYOUT;
     const int64_t need = (int64_t)d->max_prefix_len + d->T;
     if (d->paged) {
@@ -69,19 +72,25 @@ Plan make_plan(const vs_attn_desc* d) {
         return pl;
     }
     const int nrb = pl.rows_pad / kRowBlock;
-    pl.rpw = nrb >= 2 ? 2 : 1;
+    // Measured on MI355X: with many (sequence, KV head) units, eight-wave workgroups that
+    // hold two row blocks per wave and cover every CU once are fastest; with few units
+    // (one layer of one sequence) the launch is latency-bound and smaller workgroups with
+    // one row block per wave, more row groups and more key splits finish sooner.
+    const bool big = (int64_t)d->B * d->Hkv >= 48;
+    pl.rpw = d->rows_per_wave ? d->rows_per_wave : ((big && nrb >= 2) ? 2 : 1);
     const int need = (nrb + pl.rpw - 1) / pl.rpw;
+    const int max_waves = big ? kMaxWaves : 4;
     pl.waves = 1;
-    while (pl.waves < need && pl.waves < kMaxWaves) pl.waves *= 2;
+    while (pl.waves < need && pl.waves < max_waves) pl.waves *= 2;
+    if (d->waves_per_group) pl.waves = d->waves_per_group;
     pl.row_groups = (need + pl.waves - 1) / pl.waves;
     const int tiles = ((int64_t)d->max_prefix_len + d->T + kIterKeys - 1) / kIterKeys;
     const int units = d->B * d->Hkv * pl.row_groups;
     int splits = d->num_splits;
     if (splits <= 0) {
-        // enough workgroups to cover the 256 CUs (small workgroups: several per CU), but
-        // never fewer than two loop iterations per split
-        const int target = 256 * (pl.waves >= 4 ? 1 : 4 / pl.waves);
-        splits = (target + units - 1) / units;
+        // big: at most one workgroup per CU; small: ~1.5 per CU, at least two loop
+        // iterations (128 keys) per split
+        splits = big ? 256 / units : (384 + units / 2) / units;
         const int max_splits = (tiles + 1) / 2;
         if (splits > max_splits) splits = max_splits;
     }
@@ -101,7 +110,7 @@ size_t workspace_bytes(const vs_attn_desc* d, const Plan& pl) {
     return align_up(prow * d->d * sizeof(float)) + align_up(prow * 2 * sizeof(float));
 }
 
-constexpr int kArgmaxChunk = 8192;
+constexpr int kArgmaxChunk = 4096; // floats per workgroup of the scan: 256 threads x 4 x 16 bytes
 
 int32_t accept_chunks(int32_t V) { return (V + kArgmaxChunk - 1) / kArgmaxChunk; }
 
@@ -160,6 +169,7 @@ int32_t vs_attention_plan(const vs_attn_desc* desc, vs_attn_plan* plan) {
     plan->keys_per_split = pl.keys_per_split;
     plan->row_groups = pl.row_groups;
     plan->waves_per_group = pl.waves;
+    plan->rows_per_wave = pl.rpw;
     plan->workgroups = pl.total_wgs;
     plan->combine = (pl.impl == VS_IMPL_MFMA && pl.num_splits > 1) ? 1 : 0;
     return VS_OK;

@@ -79,18 +79,30 @@ def test_attention_descriptor_validation(kw, code):
 
 
 def test_plan_and_workspace_sizes():
+    # one layer of one sequence: small workgroups, one row block per wave, many splits
     rc, plan = vs.vs_attention_plan(_desc())
-    assert rc == 0 and plan.impl == vs.VS_IMPL_MFMA and plan.waves_per_group == 8 and plan.row_groups == 1
-    assert plan.keys_per_split % 32 == 0 and plan.num_splits * plan.keys_per_split >= 1696 + 60
-    assert plan.workgroups == 4 * plan.num_splits
+    assert rc == 0 and plan.impl == vs.VS_IMPL_MFMA
+    assert plan.rows_per_wave == 1 and plan.waves_per_group == 4 and plan.row_groups == 4
+    assert plan.keys_per_split % 64 == 0 and plan.num_splits * plan.keys_per_split >= 1696 + 60
+    assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
     ws = vs.vs_attention_workspace_bytes(_desc())
     assert ws >= 4 * plan.num_splits * 448 * 130 * 4
+    # many units: eight waves, two row blocks per wave, at most one workgroup per CU
+    big = _desc(B=28, stride_seq=4 * 1800 * 128)
+    rc, pb = vs.vs_attention_plan(big)
+    assert pb.rows_per_wave == 2 and pb.waves_per_group == 8 and pb.row_groups == 1
+    assert pb.num_splits == 2 and pb.workgroups == 224
+    # explicit knobs
     rc, plan1 = vs.vs_attention_plan(_desc(num_splits=1))
     assert plan1.num_splits == 1 and plan1.combine == 0 and vs.vs_attention_workspace_bytes(_desc(num_splits=1)) == 0
+    rc, pk = vs.vs_attention_plan(_desc(rows_per_wave=2, waves_per_group=8, num_splits=3))
+    assert pk.rows_per_wave == 2 and pk.waves_per_group == 8 and pk.row_groups == 1 and pk.num_splits == 3
+    assert vs.vs_attention_plan(_desc(rows_per_wave=3))[0] == -2
+    assert vs.vs_attention_plan(_desc(waves_per_group=3))[0] == -2
     rc, pg = vs.vs_attention_plan(_desc(dtype=vs.VS_F32))
     assert pg.impl == vs.VS_IMPL_GENERIC and vs.vs_attention_workspace_bytes(_desc(dtype=vs.VS_F32)) == 0
     rc, pm = vs.vs_attention_plan(_desc(Hq=32, Hkv=32, max_prefix_len=3136, capacity=3300))
-    assert pm.waves_per_group == 1 and pm.num_splits > 1
+    assert pm.waves_per_group == 2 and pm.rows_per_wave == 1 and pm.num_splits > 1
 
 
 def test_calls_reject_bad_arguments_before_any_launch():

@@ -62,6 +62,10 @@ def test_full_size_single_sequence(gu, oracle_mod, name):
     assert da.plan().impl == vs.VS_IMPL_MFMA
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=1)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=7)
+    # every kernel shape: row blocks per wave x waves per workgroup
+    for rpw in (1, 2):
+        for nw in (1, 2, 4, 8):
+            _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=3, rows_per_wave=rpw, waves_per_group=nw)
     _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
 
 
@@ -70,6 +74,8 @@ def test_c5_ragged_paged_batch(gu, oracle_mod):
     ref = oracle_mod.tree_attention(inp, threads=8)
     _run_and_check(gu, oracle_mod, inp, ref=ref)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=4)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=3, rows_per_wave=2, waves_per_group=8)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=2, rows_per_wave=1, waves_per_group=4)
 
 
 def test_layers_folded_into_batch(gu, oracle_mod):
@@ -77,6 +83,8 @@ def test_layers_folded_into_batch(gu, oracle_mod):
     cfg = dataclasses.replace(gen.CONFIGS["C3"], B=4, prefix=[1696] * 4)
     inp = gen.attention_inputs(cfg, 26)
     _run_and_check(gu, oracle_mod, inp)
+    # the launch shape the planner picks for 28 layers (two row blocks per wave, eight waves, two splits)
+    _run_and_check(gu, oracle_mod, inp, num_splits=2, rows_per_wave=2, waves_per_group=8)
 
 
 # ---------------------------------------------------------------- fuzz over shapes
@@ -106,6 +114,7 @@ def test_fuzz_shapes(gu, oracle_mod, d, g, hkv, paged, T, S, splits, B, k):
     inp = gen.attention_inputs(cfg, 1000 + k)
     ref = oracle_mod.tree_attention(inp, threads=4)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits, rows_per_wave=1 + k % 2, waves_per_group=[8, 1, 4, 2][k % 4])
     _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
 
 
