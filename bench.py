@@ -219,6 +219,14 @@ def main():
     accept_runner = build_runner(enqueue_accept)
     ms_accept, _ = timed(accept_runner, max(args.steps, 50), max(args.warmup, 5))
 
+    # a plain device copy of known size: the reference that scales rocprofv3's FETCH_SIZE /
+    # WRITE_SIZE counters when HBM traffic of the kernels above is derived from a --pmc run
+    cal_src = torch.empty(256 << 20, device=dev, dtype=torch.uint8)
+    cal_dst = torch.empty_like(cal_src)
+    with torch.cuda.stream(stream):
+        cal_dst.copy_(cal_src)
+    stream.synchronize()
+
     # ---------------------------------------------------------------- algorithmic work
     _, _, depth_h = oracle.tree_mask(parent_h[0])
     vis_pairs = int(sum(S + int(dd) + 1 for dd in depth_h))                      # visible (query, key) pairs per head
