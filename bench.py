@@ -247,6 +247,13 @@ def main():
                 "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
 
     roofline = roof(ms_folded, L)
+    # HBM bytes per folded launch measured with rocprofv3 counters (a separate --pmc run of this
+    # same command; the summary and its scaling are under profiles/)
+    try:
+        with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")) as f:
+            roofline["traffic"] = json.load(f).get(args.config, {}).get("folded_attention_call_bytes")
+    except OSError:
+        pass
     roofline.update({"kernel": "attn_mfma_kernel (+ split combine)", "launch": f"{L} layers folded as batch entries",
                      "us_per_launch": round(ms_folded * 1e3, 2), "workgroups": planL.workgroups,
                      "num_splits": planL.num_splits,
