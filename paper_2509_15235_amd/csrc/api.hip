@@ -72,23 +72,55 @@ Plan make_plan(const vs_attn_desc* d) {
         return pl;
     }
     const int nrb = pl.rows_pad / kRowBlock;
-    // Measured on MI355X: with many (sequence, KV head) units, eight-wave workgroups that
-    // hold two row blocks per wave and cover every CU once are fastest; with few units
-    // (one layer of one sequence) the launch is latency-bound and smaller workgroups with
-    // one row block per wave, more row groups and more key splits finish sooner.
-    const bool big = (int64_t)d->B * d->Hkv >= 48;
-    pl.rpw = d->rows_per_wave ? d->rows_per_wave : ((big && nrb >= 2) ? 2 : 1);
-    const int need = (nrb + pl.rpw - 1) / pl.rpw;
-    const int max_waves = big ? kMaxWaves : 4;
-    pl.waves = 1;
-    while (pl.waves < need && pl.waves < max_waves) pl.waves *= 2;
-    if (d->waves_per_group) pl.waves = d->waves_per_group;
-    pl.row_groups = (need + pl.waves - 1) / pl.waves;
     const int tiles = ((int64_t)d->max_prefix_len + d->T + kIterKeys - 1) / kIterKeys;
-    const int units = d->B * d->Hkv * pl.row_groups;
-    int splits = d->num_splits;
+    const int units0 = d->B * d->Hkv;
+    // Launch shape, from measurements on MI355X (C2..C5-shaped inputs):
+    //  * few units (one layer of one sequence): latency-bound; one row block per wave, at
+    //    most four waves, more row groups and about 1.5 workgroups per CU;
+    //  * many units: either eight waves x two row blocks with key splits that fill the CUs
+    //    once (best for long sequences: fewest LDS reads per MFMA, but partials + combine),
+    //    or eight waves x one row block with the rows split over workgroups (no partials
+    //    when that alone fills the machine). A small cost model in microseconds picks.
+    const bool big = units0 >= 48;
+    int rpw = d->rows_per_wave, waves = d->waves_per_group, splits = d->num_splits;
+    if (!big || nrb <= 4) {
+        if (!rpw) rpw = 1;
+        if (!waves) {
+            const int need1 = (nrb + rpw - 1) / rpw;
+            waves = 1;
+            while (waves < need1 && waves < 4) waves *= 2;
+        }
+    } else if (!rpw) {
+        auto cost = [&](int r, int* out_splits) {
+            const int cap_blocks = kMaxWaves * r;                       // row blocks per workgroup
+            const int rg = (nrb + cap_blocks - 1) / cap_blocks;
+            const int blocks = (nrb + rg - 1) / rg;                     // ... actually used
+            const int wgs = units0 * rg;
+            int sp = splits > 0 ? splits : (wgs >= 256 ? 1 : 256 / wgs);
+            if (sp > (tiles + 1) / 2) sp = (tiles + 1) / 2;
+            if (sp < 1) sp = 1;
+            const double per_tile = (r == 2 ? 2.2 * blocks / 14.0 : 1.3 * blocks / 7.0) * 2.0; // per 64 keys
+            const double rounds = (double)((wgs * sp + 255) / 256);
+            *out_splits = sp;
+            return rounds * per_tile * ((tiles + sp - 1) / sp) + (sp > 1 ? 16.0 : 4.0);
+        };
+        int s1 = 1, s2 = 1;
+        const double c1 = cost(1, &s1), c2 = nrb >= 2 ? cost(2, &s2) : 1e30;
+        rpw = c2 < c1 ? 2 : 1;
+        if (splits <= 0) splits = rpw == 2 ? s2 : s1;
+    }
+    if (!waves) {
+        const int need2 = (nrb + rpw - 1) / rpw;
+        waves = 1;
+        while (waves < need2 && waves < kMaxWaves) waves *= 2;
+    }
+    pl.rpw = rpw;
+    pl.waves = waves;
+    const int need = (nrb + pl.rpw - 1) / pl.rpw;
+    pl.row_groups = (need + pl.waves - 1) / pl.waves;
+    const int units = units0 * pl.row_groups;
     if (splits <= 0) {
-        // big: at most one workgroup per CU; small: ~1.5 per CU, at least two loop
+        // large: fill the CUs once; small: ~1.5 workgroups per CU, at least two loop
         // iterations (128 keys) per split
         splits = big ? 256 / units : (384 + units / 2) / units;
         const int max_splits = (tiles + 1) / 2;

@@ -38,9 +38,9 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-// s_waitcnt immediate that waits for every outstanding vector-memory load (vmcnt = 0) and
-// nothing else (expcnt = 7, lgkmcnt = 15 are their maxima).
-constexpr int kWaitVm0 = 0x0F70;
+// s_waitcnt immediate that waits until at most n vector-memory loads are outstanding and
+// for nothing else (expcnt = 7, lgkmcnt = 15 are their maxima). Loads return in order.
+constexpr int wait_vm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 constexpr float kLazy = 8.f; // log2 slack of the running softmax reference
 
@@ -89,7 +89,16 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     constexpr bool QL = (RPW == 2 && NW == 8);
     constexpr int QR0 = QL ? KS / 2 : KS;          // k-steps of row block 0 whose queries stay in registers
     constexpr int NQL = QL ? (KS - QR0) + KS : 0;  // LDS query slots (1 KB each) per wave
-    constexpr int NBUF = STAGGER ? 3 : 2;
+    // Tile copies run PD iterations ahead of their use (deeper when LDS allows: short
+    // iterations do not cover the memory latency with a single tile in flight).
+    constexpr int LPT = 2 * IPW;                   // load instructions per wave and tile copy
+    // Direct global-to-LDS loads need no registers but are issued slowly; where registers
+    // are free (no LDS-resident queries) tiles are staged through registers instead, one
+    // iteration ahead.
+    constexpr bool DIRECT = QL || IPW > 4;
+    constexpr int PD = 1;
+    constexpr int NBUF = PD + (STAGGER ? 2 : 1);
+    static_assert((PD - 1) * LPT < 64, "vmcnt has six bits");
 
     // Tiles live in LDS in 16-byte chunks placed so that every access is conflict-free and
     // every address is "per-lane constant + immediate". A direct-to-LDS load instruction
@@ -150,6 +159,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     const int stride_tok = (int)p.stride_tok;           // host guarantees 32-bit lane offsets
     const int krow_l = lane & 15, kcol_l = (lane >> 4) * 8;
     const int vrow_l = 4 * (lane >> 4) + ((lane & 15) >> 2), vcol_l = (lane & 3) * 8;
+    u32x4 kreg[DIRECT ? 1 : IPW], vreg[DIRECT ? 1 : IPW]; // staged tile (register path)
     auto fetch = [&](int kt, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < IPW; ++j) {
@@ -168,12 +178,30 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
                 }
                 const uint32_t koff = (uint32_t)(ktok * stride_tok + c0 + kcol_l);
                 const uint32_t voff = (uint32_t)(vtok * stride_tok + c0 + vcol_l);
-                __builtin_amdgcn_global_load_lds(kbase + base + koff, (lds_void*)(sK[buf] + i * 512), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(vbase + base + voff, (lds_void*)(sV[buf] + i * 512), 16, 0, 0);
+                if constexpr (DIRECT) {
+                    __builtin_amdgcn_global_load_lds(kbase + base + koff, (lds_void*)(sK[buf] + i * 512), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds(vbase + base + voff, (lds_void*)(sV[buf] + i * 512), 16, 0, 0);
+                } else {
+                    kreg[j] = __builtin_nontemporal_load((const u32x4*)(kbase + base + koff));
+                    vreg[j] = __builtin_nontemporal_load((const u32x4*)(vbase + base + voff));
+                }
             }
         }
     };
-    fetch(k0, 0); // in flight while the queries are loaded
+    // register path: write the staged tile into LDS buffer `buf` (same chunk placement)
+    auto stash = [&](int buf) __attribute__((always_inline)) {
+        if constexpr (!DIRECT) {
+#pragma unroll
+            for (int j = 0; j < IPW; ++j) {
+                const int i = wave * IPW + j;
+                if (i < IPT) {
+                    *(u32x4*)(sK[buf] + i * 512 + lane * 8) = kreg[j];
+                    *(u32x4*)(sV[buf] + i * 512 + lane * 8) = vreg[j];
+                }
+            }
+        }
+    };
+    fetch(k0, 0); // in flight while the queries are loaded; tokens past the end are clamped
 
     // ---- this wave's rows, their masks and queries
     const int row_base = rg * p.rows_per_group + wave * (RPW * kRowBlock);
@@ -348,7 +376,11 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
         }
     };
 
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    // the other tiles of the prefetch window; then wait for tile 0, the queries and masks
+#pragma unroll
+    for (int t = 1; t < PD; ++t) fetch(k0 + t * ITER, t);
+    __builtin_amdgcn_s_waitcnt(wait_vm((PD - 1) * LPT));
+    stash(0);
     __syncthreads();
 
     // Iterations whose keys end at or before min(S, k1) are pure prefix; the rest take the
@@ -361,7 +393,10 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     auto step = [&](auto late_tag, auto masked_tag) __attribute__((always_inline)) {
         constexpr bool LATE = decltype(late_tag)::value;
         const int nxt = (buf + 1 == NBUF) ? 0 : buf + 1;
-        if (kt + ITER < k1) fetch(kt + ITER, nxt);
+        // copy the tile PD iterations ahead into a buffer whose readers are all done; issued
+        // even past the end of the range (clamped tokens) so that every wave always has the
+        // same number of loads in flight and the counted wait below stays exact
+        if (PD > 1 || kt + ITER < k1) fetch(kt + PD * ITER, (buf + PD) % NBUF);
         if (wave_active) {
             if constexpr (LATE) {
                 if (kt > k0) pv(sV[prv]); // previous iteration's probabilities, kept in pf
@@ -376,7 +411,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
                 }
             }
         }
-        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        __builtin_amdgcn_s_waitcnt(wait_vm((PD - 1) * LPT)); // the next tile has arrived
+        stash(nxt);
         __syncthreads();
         prv = buf;
         buf = nxt;

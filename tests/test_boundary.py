@@ -87,11 +87,16 @@ def test_plan_and_workspace_sizes():
     assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
     ws = vs.vs_attention_workspace_bytes(_desc())
     assert ws >= 4 * plan.num_splits * 448 * 130 * 4
-    # many units: eight waves, two row blocks per wave, at most one workgroup per CU
+    # many short units: eight waves, rows split over two workgroups, no key split, no combine
     big = _desc(B=28, stride_seq=4 * 1800 * 128)
     rc, pb = vs.vs_attention_plan(big)
-    assert pb.rows_per_wave == 2 and pb.waves_per_group == 8 and pb.row_groups == 1
-    assert pb.num_splits == 2 and pb.workgroups == 224
+    assert pb.rows_per_wave == 1 and pb.waves_per_group == 8 and pb.row_groups == 2
+    assert pb.num_splits == 1 and pb.workgroups == 224 and pb.combine == 0
+    # many long units: two row blocks per wave and key splits that fill the CUs once
+    long_ = _desc(B=28, max_prefix_len=6684, capacity=6800, stride_seq=4 * 6800 * 128, stride_head=6800 * 128)
+    rc, pl = vs.vs_attention_plan(long_)
+    assert pl.rows_per_wave == 2 and pl.waves_per_group == 8 and pl.row_groups == 1
+    assert pl.num_splits == 2 and pl.workgroups == 224 and pl.combine == 1
     # explicit knobs
     rc, plan1 = vs.vs_attention_plan(_desc(num_splits=1))
     assert plan1.num_splits == 1 and plan1.combine == 0 and vs.vs_attention_workspace_bytes(_desc(num_splits=1)) == 0

@@ -83,7 +83,8 @@ def test_layers_folded_into_batch(gu, oracle_mod):
     cfg = dataclasses.replace(gen.CONFIGS["C3"], B=4, prefix=[1696] * 4)
     inp = gen.attention_inputs(cfg, 26)
     _run_and_check(gu, oracle_mod, inp)
-    # the launch shape the planner picks for 28 layers (two row blocks per wave, eight waves, two splits)
+    # the launch shapes the planner picks for 28 layers of short / long sequences
+    _run_and_check(gu, oracle_mod, inp, num_splits=1, rows_per_wave=1, waves_per_group=8)
     _run_and_check(gu, oracle_mod, inp, num_splits=2, rows_per_wave=2, waves_per_group=8)
 
 
