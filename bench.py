@@ -254,7 +254,11 @@ def main():
             roofline["traffic"] = json.load(f).get(args.config, {}).get("folded_attention_call_bytes")
     except OSError:
         pass
-    roofline.update({"kernel": "attn_mfma_kernel (+ split combine)", "launch": f"{L} layers folded as batch entries",
+    def kernel_name(pl):
+        k = "attn_mfma_pipe_kernel" if pl.schedule == vs.VS_SCHED_PIPELINED else "attn_mfma_kernel"
+        return k + (" + attn_combine_kernel" if pl.combine else "")
+
+    roofline.update({"kernel": kernel_name(planL), "launch": f"{L} layers folded as batch entries",
                      "us_per_launch": round(ms_folded * 1e3, 2), "workgroups": planL.workgroups,
                      "num_splits": planL.num_splits,
                      "tflops": round(flops_layer * L / (ms_folded * 1e-3) / 1e12, 2),
@@ -262,7 +266,7 @@ def main():
                      "frac_of_hbm_peak": round(bytes_layer * L / (ms_folded * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
     per_layer = roof(ms_single, 1)
     per_layer.update({"launch": "one layer, B=1", "us_per_launch": round(ms_single * 1e3, 2),
-                      "workgroups": plan1.workgroups, "num_splits": plan1.num_splits})
+                      "workgroups": plan1.workgroups, "num_splits": plan1.num_splits, "kernel": kernel_name(plan1)})
     argmax_gbs = logit_bytes / (ms_accept * 1e-3) / 1e9
     argmax = {"bound": "hbm", "achieved": round(argmax_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
               "frac": round(argmax_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(ms_accept * 1e3, 2),

@@ -68,6 +68,11 @@ typedef enum vs_dtype { VS_BF16 = 0, VS_F32 = 1 } vs_dtype;
 /* Which attention kernel to run. AUTO picks MFMA for bf16 and GENERIC for fp32. */
 typedef enum vs_attn_impl { VS_IMPL_AUTO = 0, VS_IMPL_GENERIC = 1, VS_IMPL_MFMA = 2 } vs_attn_impl;
 
+/* How the MFMA kernel orders a tile's three stages (scores, softmax, output update):
+ * LOOP runs them back to back; PIPELINED overlaps the matrix-core work of the
+ * neighbouring tiles with the current tile's softmax. Same results up to fp32 rounding. */
+typedef enum vs_attn_schedule { VS_SCHED_AUTO = 0, VS_SCHED_LOOP = 1, VS_SCHED_PIPELINED = 2 } vs_attn_schedule;
+
 int32_t vs_version(void);
 const char* vs_strerror(int32_t err);       /* static string for a vs_error */
 const char* vs_status_string(int32_t code); /* static string for a vs_status */
@@ -128,6 +133,8 @@ typedef struct vs_attn_desc {
     int32_t num_splits;     /* key splits per (sequence, KV head); 0 = choose */
     int32_t rows_per_wave;  /* MFMA path: 32-row blocks per wave, 1 or 2; 0 = choose */
     int32_t waves_per_group; /* MFMA path: waves per workgroup, 1, 2, 4 or 8; 0 = choose */
+    int32_t schedule;       /* MFMA path: vs_attn_schedule; PIPELINED needs rows_per_wave 0 or 1
+                               and waves_per_group 0, 4 or 8 */
 } vs_attn_desc;
 
 /* What a call with this descriptor would launch (for tests and reports). */
@@ -140,6 +147,7 @@ typedef struct vs_attn_plan {
     int32_t rows_per_wave;   /* 32-row blocks per wave (MFMA path) */
     int32_t workgroups;      /* main kernel grid size */
     int32_t combine;         /* 1 if a split-combine kernel follows */
+    int32_t schedule;        /* VS_SCHED_LOOP or VS_SCHED_PIPELINED (MFMA path), else 0 */
 } vs_attn_plan;
 
 int32_t vs_attention_plan(const vs_attn_desc* desc, vs_attn_plan* plan); /* both host */

@@ -9,6 +9,7 @@ _LIB_PATH = os.path.join(_HERE, "libvispec_verify.so")
 
 VS_BF16, VS_F32 = 0, 1
 VS_IMPL_AUTO, VS_IMPL_GENERIC, VS_IMPL_MFMA = 0, 1, 2
+VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "vs_version", "vs_strerror", "vs_status_string", "vs_tree_validate_host", "vs_tree_mask_build",
@@ -32,6 +33,7 @@ class AttnDesc(ctypes.Structure):
         ("stride_seq", ctypes.c_int64), ("stride_block", ctypes.c_int64), ("stride_head", ctypes.c_int64),
         ("stride_tok", ctypes.c_int64), ("block_table", ctypes.c_void_p), ("impl", ctypes.c_int32),
         ("num_splits", ctypes.c_int32), ("rows_per_wave", ctypes.c_int32), ("waves_per_group", ctypes.c_int32),
+        ("schedule", ctypes.c_int32),
     ]
 
 
@@ -40,7 +42,7 @@ class AttnPlan(ctypes.Structure):
         ("impl", ctypes.c_int32), ("num_splits", ctypes.c_int32), ("keys_per_split", ctypes.c_int32),
         ("row_groups", ctypes.c_int32), ("waves_per_group", ctypes.c_int32), ("rows_per_wave", ctypes.c_int32),
         ("workgroups", ctypes.c_int32),
-        ("combine", ctypes.c_int32),
+        ("combine", ctypes.c_int32), ("schedule", ctypes.c_int32),
     ]
 
 

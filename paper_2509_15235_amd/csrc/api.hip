@@ -15,7 +15,7 @@ inline bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 struct Plan {
-    int32_t impl, rpw, waves, row_groups, rows, rows_pad, num_splits, keys_per_split, total_wgs;
+    int32_t impl, rpw, waves, row_groups, rows, rows_pad, num_splits, keys_per_split, total_wgs, schedule;
 };
 
 // Shape / dtype / layout checks that need no device. Returns VS_OK or a vs_error.
@@ -33,6 +33,13 @@ int32_t check_desc(const vs_attn_desc* d) {
     if (d->waves_per_group != 0 && d->waves_per_group != 1 && d->waves_per_group != 2 && d->waves_per_group != 4 &&
         d->waves_per_group != 8)
         return VS_ERR_SHAPE;
+    if (d->schedule != VS_SCHED_AUTO && d->schedule != VS_SCHED_LOOP && d->schedule != VS_SCHED_PIPELINED)
+        return VS_ERR_SHAPE;
+    if (d->schedule == VS_SCHED_PIPELINED) {
+        // the pipelined kernel exists for one row block per wave and four or eight waves
+        if (d->rows_per_wave == 2) return VS_ERR_SHAPE;
+        if (d->waves_per_group != 0 && d->waves_per_group != 4 && d->waves_per_group != 8) return VS_ERR_SHAPE;
+    }
     if (d->stride_head < 0 || d->stride_tok < d->d) return VS_ERR_LAYOUT;
     const int64_t need = (int64_t)d->max_prefix_len + d->T;
     if (d->paged) {
@@ -75,15 +82,29 @@ Plan make_plan(const vs_attn_desc* d) {
     const int tiles = ((int64_t)d->max_prefix_len + d->T + kIterKeys - 1) / kIterKeys;
     const int units0 = d->B * d->Hkv;
     // Launch shape, from measurements on MI355X (C2..C5-shaped inputs):
-    //  * few units (one layer of one sequence): latency-bound; one row block per wave, at
-    //    most four waves, more row groups and about 1.5 workgroups per CU;
-    //  * many units: either eight waves x two row blocks with key splits that fill the CUs
-    //    once (best for long sequences: fewest LDS reads per MFMA, but partials + combine),
-    //    or eight waves x one row block with the rows split over workgroups (no partials
-    //    when that alone fills the machine). A small cost model in microseconds picks.
+    //  * few units (one layer of one sequence): latency-bound; straight-loop kernel, one
+    //    row block per wave, at most four waves, more row groups and about 1.5 workgroups
+    //    per CU;
+    //  * many units: the software-pipelined kernel with one row block per wave, the rows
+    //    split over row groups of eight (or four) waves, and key splits only when units x
+    //    row groups leave CUs empty. No partial results when that alone fills the machine.
+    //  * a caller who fixes rows_per_wave = 2 or a wave count the pipelined kernel does not
+    //    have gets the straight loop; with two row blocks per wave a small cost model in
+    //    microseconds still chooses the key splits.
     const bool big = units0 >= 48;
     int rpw = d->rows_per_wave, waves = d->waves_per_group, splits = d->num_splits;
-    if (!big || nrb <= 4) {
+    const bool pipe_ok = (rpw == 0 || rpw == 1) && (waves == 0 || waves == 4 || waves == 8);
+    pl.schedule = d->schedule == VS_SCHED_AUTO ? (big && pipe_ok ? VS_SCHED_PIPELINED : VS_SCHED_LOOP) : d->schedule;
+    if (pl.schedule == VS_SCHED_PIPELINED) {
+        rpw = 1;
+        if (!waves) waves = nrb > 4 ? 8 : 4;
+        if (splits <= 0) {
+            const int wgs = units0 * ((nrb + waves - 1) / waves);
+            splits = wgs >= 200 ? 1 : 256 / wgs;
+            const int max_splits = (tiles + 3) / 4; // at least four iterations per split
+            if (splits > max_splits) splits = max_splits;
+        }
+    } else if (!big || nrb <= 4) {
         if (!rpw) rpw = 1;
         if (!waves) {
             const int need1 = (nrb + rpw - 1) / rpw;
@@ -204,6 +225,7 @@ int32_t vs_attention_plan(const vs_attn_desc* desc, vs_attn_plan* plan) {
     plan->rows_per_wave = pl.rpw;
     plan->workgroups = pl.total_wgs;
     plan->combine = (pl.impl == VS_IMPL_MFMA && pl.num_splits > 1) ? 1 : 0;
+    plan->schedule = pl.schedule;
     return VS_OK;
 }
 
@@ -273,7 +295,8 @@ int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const 
     if (pl.impl == VS_IMPL_GENERIC) {
         e = launch_attention_generic(p, desc->dtype, s);
     } else {
-        e = launch_attention_mfma(p, pl.rpw, pl.waves, s);
+        e = pl.schedule == VS_SCHED_PIPELINED ? launch_attention_mfma_pipe(p, pl.rpw, pl.waves, s)
+                                              : launch_attention_mfma(p, pl.rpw, pl.waves, s);
         if (e == hipSuccess && pl.num_splits > 1) e = launch_attention_combine(p, desc->dtype, s);
     }
     return e == hipSuccess ? VS_OK : VS_ERR_HIP;

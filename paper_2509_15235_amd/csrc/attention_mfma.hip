@@ -9,8 +9,10 @@
 // One workgroup owns (sequence, KV head, key split, row group); each of its NW waves
 // owns RPW blocks of 32 rows and keeps their queries, running softmax state and output
 // accumulators in registers for the whole key range. Keys stream through double-buffered
-// LDS tiles of 32 keys that are filled by direct global-to-LDS loads (no staging
-// registers); the 16-byte chunks of K and V are placed so that reads are conflict-free.
+// LDS tiles of 32 keys; the 16-byte chunks of K and V are placed so that fragment reads
+// are conflict-free. Where registers allow, a tile is fetched one iteration ahead into
+// registers (1 KB of consecutive memory per load instruction) and then scattered into
+// LDS; the register-starved shapes use direct global-to-LDS loads instead.
 //
 // Per tile and row block (v_mfma_f32_32x32x16_bf16, A = 32x16, B = 16x32, C = 32x32):
 //   S^T[key][row] = K[key][:] . Q[row][:]        A = K tile (LDS), B = Q (registers)
@@ -26,45 +28,11 @@
 // combine kernel merges them.
 #include <type_traits>
 
-#include "vs_device.h"
+#include "attn_mfma_common.h"
 
 namespace vs {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-typedef __attribute__((address_space(3))) void lds_void;
-
-// s_waitcnt immediate that waits until at most n vector-memory loads are outstanding and
-// for nothing else (expcnt = 7, lgkmcnt = 15 are their maxima). Loads return in order.
-constexpr int wait_vm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
-
-constexpr float kLazy = 8.f; // log2 slack of the running softmax reference
-
-// max / sum over the two 32-lane halves, result in every lane (v_permlane32_swap)
-__device__ __forceinline__ float half_max(float x) {
-    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float half_sum(float x) {
-    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// Partial results of one (sequence, KV head, split, 32-row block): D/32 accumulator blocks,
-// each stored as 4 x [64 lanes x 4 floats] (register r = 4*q4 + e of lane l at
-// ((db*4 + q4)*64 + l)*4 + e), followed elsewhere by 32 x (max, sum).
-__device__ __forceinline__ int64_t part_block(const AttnParams& p, int64_t unit, int split, int rbk) {
-    return (unit * p.num_splits + split) * (int64_t)(p.rows_pad / kRowBlock) + rbk;
-}
-// (max, sum) pairs are grouped per row block with the splits adjacent: index of the
-// first of the 32 rows of (unit, rbk, split), in pairs.
-__device__ __forceinline__ int64_t ml_block(const AttnParams& p, int64_t unit, int split, int rbk) {
-    return ((unit * (p.rows_pad / kRowBlock) + rbk) * p.num_splits + split) * (int64_t)kRowBlock;
-}
 
 template <int D, int RPW, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) {
@@ -95,7 +63,11 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     // Direct global-to-LDS loads need no registers but are issued slowly; where registers
     // are free (no LDS-resident queries) tiles are staged through registers instead, one
     // iteration ahead.
-    constexpr bool DIRECT = QL || IPW > 4;
+    constexpr bool DIRECT = QL || IPW > 8 || (RPW == 2 && IPW > 4);
+    // Staged copies fetch whole rows: one load instruction of a wave reads 1 KB of consecutive
+    // memory (RPI tokens of D channels; lane q -> row q / LPR, 16-byte chunk q % LPR).
+    constexpr int LPR = D / 8;
+    constexpr int RPI = 64 / LPR;
     constexpr int PD = 1;
     constexpr int NBUF = PD + (STAGGER ? 2 : 1);
     static_assert((PD - 1) * LPT < 64, "vmcnt has six bits");
@@ -159,44 +131,72 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     const int stride_tok = (int)p.stride_tok;           // host guarantees 32-bit lane offsets
     const int krow_l = lane & 15, kcol_l = (lane >> 4) * 8;
     const int vrow_l = 4 * (lane >> 4) + ((lane & 15) >> 2), vcol_l = (lane & 3) * 8;
+    // Register path: where chunk c (16 bytes) of row r of a 32-key block lives in LDS. Same
+    // placement as above except that K rows are XOR-swizzled by 4*(c%4), which turns the
+    // 16-way bank conflict of writing one row's chunks into a 4-way one and leaves the
+    // fragment reads (16 rows at one chunk) conflict-free:
+    //   K: ((r/16)*DB + c/4) * 1024 + (c%4) * 256 + ((r%16) ^ 4*(c%4)) * 16
+    //   V: ((r/16)*DB + c/4) * 1024 + (4*(r%16) + c%4) * 16
+    const int lrow = lane / LPR, lchunk = lane % LPR;
     u32x4 kreg[DIRECT ? 1 : IPW], vreg[DIRECT ? 1 : IPW]; // staged tile (register path)
+    uint32_t k_st[DIRECT ? 1 : IPW], v_st[DIRECT ? 1 : IPW]; // LDS byte offsets inside one buffer
+    if constexpr (!DIRECT) {
+#pragma unroll
+        for (int j = 0; j < IPW; ++j) {
+            const int i = wave * IPW + j;
+            const int r = (i % BPS) * RPI + lrow, c = lchunk;
+            k_st[j] = (uint32_t)((i / BPS) * (SUB * 2) + ((r >> 4) * DB + (c >> 2)) * 1024 + (c & 3) * 256 +
+                                 (((r & 15) ^ (4 * (c & 3))) * 16));
+            v_st[j] = (uint32_t)((i / BPS) * (SUB * 2) + ((r >> 4) * DB + (c >> 2)) * 1024 + (4 * (r & 15) + (c & 3)) * 16);
+        }
+    }
     auto fetch = [&](int kt, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < IPW; ++j) {
             const int i = wave * IPW + j; // block index, uniform per wave
             if (i < IPT) {
-                const int r0 = kt + kTileKeys * (i / BPS) + 16 * ((i % BPS) / DB);
-                const int c0 = 32 * (i % DB);
-                int ktok = min(r0 + krow_l, k1 - 1), vtok = min(r0 + vrow_l, k1 - 1);
-                int64_t base = head_base;
-                if (p.paged) {
-                    int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (min(r0, k1 - 1) >> p.block_shift)];
-                    if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
-                    base += (int64_t)blk * p.stride_block;
-                    ktok &= p.block_size - 1;
-                    vtok &= p.block_size - 1;
-                }
-                const uint32_t koff = (uint32_t)(ktok * stride_tok + c0 + kcol_l);
-                const uint32_t voff = (uint32_t)(vtok * stride_tok + c0 + vcol_l);
                 if constexpr (DIRECT) {
+                    const int r0 = kt + kTileKeys * (i / BPS) + 16 * ((i % BPS) / DB);
+                    const int c0 = 32 * (i % DB);
+                    int ktok = min(r0 + krow_l, k1 - 1), vtok = min(r0 + vrow_l, k1 - 1);
+                    int64_t base = head_base;
+                    if (p.paged) {
+                        int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (min(r0, k1 - 1) >> p.block_shift)];
+                        if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
+                        base += (int64_t)blk * p.stride_block;
+                        ktok &= p.block_size - 1;
+                        vtok &= p.block_size - 1;
+                    }
+                    const uint32_t koff = (uint32_t)(ktok * stride_tok + c0 + kcol_l);
+                    const uint32_t voff = (uint32_t)(vtok * stride_tok + c0 + vcol_l);
                     __builtin_amdgcn_global_load_lds(kbase + base + koff, (lds_void*)(sK[buf] + i * 512), 16, 0, 0);
                     __builtin_amdgcn_global_load_lds(vbase + base + voff, (lds_void*)(sV[buf] + i * 512), 16, 0, 0);
                 } else {
-                    kreg[j] = __builtin_nontemporal_load((const u32x4*)(kbase + base + koff));
-                    vreg[j] = __builtin_nontemporal_load((const u32x4*)(vbase + base + voff));
+                    const int r0 = kt + kTileKeys * (i / BPS) + RPI * (i % BPS); // RPI divides 16: one page
+                    int tok = min(r0 + lrow, k1 - 1);
+                    int64_t base = head_base;
+                    if (p.paged) {
+                        int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (min(r0, k1 - 1) >> p.block_shift)];
+                        if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
+                        base += (int64_t)blk * p.stride_block;
+                        tok &= p.block_size - 1;
+                    }
+                    const uint32_t off = (uint32_t)(tok * stride_tok + lchunk * 8);
+                    kreg[j] = *(const u32x4*)(kbase + base + off);
+                    vreg[j] = *(const u32x4*)(vbase + base + off);
                 }
             }
         }
     };
-    // register path: write the staged tile into LDS buffer `buf` (same chunk placement)
+    // register path: write the staged tile into LDS buffer `buf`
     auto stash = [&](int buf) __attribute__((always_inline)) {
         if constexpr (!DIRECT) {
 #pragma unroll
             for (int j = 0; j < IPW; ++j) {
                 const int i = wave * IPW + j;
                 if (i < IPT) {
-                    *(u32x4*)(sK[buf] + i * 512 + lane * 8) = kreg[j];
-                    *(u32x4*)(sV[buf] + i * 512 + lane * 8) = vreg[j];
+                    *(u32x4*)((char*)sK[buf] + k_st[j]) = kreg[j];
+                    *(u32x4*)((char*)sV[buf] + v_st[j]) = vreg[j];
                 }
             }
         }
@@ -243,7 +243,10 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     }
 
     // per-lane LDS offsets (elements); everything else is a compile-time immediate
-    const int k_lane = (col >> 4) * (DB * 512) + half * 128 + (col & 15) * 8; // + ks*256
+    // K fragment of k-step ks (chunk 2*ks + half of row `col`): k_lane[ks & 1] + ks*256
+    const int kx0 = DIRECT ? 0 : 4 * half, kx1 = DIRECT ? 0 : 8 + 4 * half;
+    const int k_lane[2] = {(col >> 4) * (DB * 512) + half * 128 + ((col & 15) ^ kx0) * 8,
+                           (col >> 4) * (DB * 512) + half * 128 + ((col & 15) ^ kx1) * 8};
     const int t16 = lane & 15;                                               // transposing V read: 16-lane groups
     const int v_lane = half * 128 + (t16 >> 2) * 32 + ((lane >> 4) & 1) * 16 + ((t16 >> 1) & 1) * 8 + (t16 & 1) * 4;
     //                 + sl*(DB*512) + db*512 + u*256
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     bf16x8 pf[RPW][2];
     auto score = [&](auto masked_tag, int kt, const uint16_t* kblock) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const uint16_t* tK = kblock + k_lane;
+        const uint16_t* tK[2] = {kblock + k_lane[0], kblock + k_lane[1]};
         // ---- per row block: S^T = K . Q^T, mask, online softmax, P as a B operand.
         // Lane (col, half) holds keys 8*(r/4) + 4*half + r%4 of row `col`.
         // Each K fragment is read from LDS once and feeds every row block. The reads run
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
             for (int r = 0; r < 16; ++r) sc[rb][r] = 0.f;
         u32x4 ka[PF + 1], qa[PF + 1][RPW]; // fragment ring buffers (only LDS-resident queries use qa)
         auto load_frags = [&](int ks) __attribute__((always_inline)) {
-            ka[ks % (PF + 1)] = *(const u32x4*)(tK + ks * 256);
+            ka[ks % (PF + 1)] = *(const u32x4*)(tK[ks & 1] + ks * 256);
 #pragma unroll
             for (int rb = 0; rb < RPW; ++rb) {
                 if (QL && (rb == 1 || ks >= QR0)) {

@@ -1,0 +1,52 @@
+// Pieces shared by the matrix-core attention kernels: vector types, cross-half reductions
+// and the workspace layout of split partial results.
+#pragma once
+
+#include "vs_device.h"
+
+namespace vs {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+typedef __attribute__((address_space(3))) void lds_void;
+
+// s_waitcnt immediate that waits until at most n vector-memory loads are outstanding and
+// for nothing else (expcnt = 7, lgkmcnt = 15 are their maxima). Loads return in order.
+constexpr int wait_vm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
+constexpr float kLazy = 8.f; // log2 slack of the running softmax reference
+
+// max(a, b, c) as one instruction. (fmaxf chains first pass every operand through a
+// canonicalising v_max x, x because the compiler cannot prove MFMA results are not
+// signalling NaNs; the hardware instruction itself handles them.)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// max / sum over the two 32-lane halves, result in every lane (v_permlane32_swap)
+__device__ __forceinline__ float half_max(float x) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Partial results of one (sequence, KV head, split, 32-row block): D/32 accumulator blocks,
+// each stored as 4 x [64 lanes x 4 floats] (register r = 4*q4 + e of lane l at
+// ((db*4 + q4)*64 + l)*4 + e), followed elsewhere by 32 x (max, sum).
+__device__ __forceinline__ int64_t part_block(const AttnParams& p, int64_t unit, int split, int rbk) {
+    return (unit * p.num_splits + split) * (int64_t)(p.rows_pad / kRowBlock) + rbk;
+}
+// (max, sum) pairs are grouped per row block with the splits adjacent: index of the
+// first of the 32 rows of (unit, rbk, split), in pairs.
+__device__ __forceinline__ int64_t ml_block(const AttnParams& p, int64_t unit, int split, int rbk) {
+    return ((unit * (p.rows_pad / kRowBlock) + rbk) * p.num_splits + split) * (int64_t)kRowBlock;
+}
+
+} // namespace vs

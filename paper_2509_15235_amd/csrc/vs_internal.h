@@ -76,6 +76,8 @@ hipError_t launch_tree_mask(const int32_t* parent, int32_t B, int32_t T, uint64_
                             int32_t* depth, int32_t* status, hipStream_t s);
 hipError_t launch_attention_generic(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_attention_mfma(const AttnParams& p, int rpw, int waves, hipStream_t s);
+bool attention_pipe_supported(int rpw, int waves);
+hipError_t launch_attention_mfma_pipe(const AttnParams& p, int rpw, int waves, hipStream_t s);
 hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 

@@ -23,7 +23,7 @@ class DeviceAttn:
     """Device copies of a gen.AttnInputs plus the matching descriptor."""
 
     def __init__(self, inp, impl=vs.VS_IMPL_AUTO, num_splits=0, max_prefix_len=None, rows_per_wave=0,
-                 waves_per_group=0):
+                 waves_per_group=0, schedule=0):
         cfg = inp.cfg
         self.inp = inp
         bf = cfg.dtype == "bf16"
@@ -45,6 +45,7 @@ class DeviceAttn:
         d.num_splits = num_splits
         d.rows_per_wave = rows_per_wave
         d.waves_per_group = waves_per_group
+        d.schedule = schedule
         if inp.block_table is None:
             cap = inp.k_cache.shape[2]
             d.paged = 0

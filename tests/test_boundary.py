@@ -70,6 +70,9 @@ def _desc(**kw):
     ({"paged": 1, "block_size": 24, "max_blocks": 200, "num_blocks": 300, "block_table": 4096}, -6),
     ({"paged": 1, "block_size": 16, "max_blocks": 10, "num_blocks": 300, "block_table": 4096}, -6),
     ({"num_splits": -1}, -2),
+    ({"schedule": 3}, -2), ({"schedule": vs.VS_SCHED_PIPELINED, "rows_per_wave": 2}, -2),
+    ({"schedule": vs.VS_SCHED_PIPELINED, "waves_per_group": 2}, -2),
+    ({"schedule": vs.VS_SCHED_PIPELINED, "waves_per_group": 4}, 0), ({"schedule": vs.VS_SCHED_LOOP}, 0),
 ])
 def test_attention_descriptor_validation(kw, code):
     rc, plan = vs.vs_attention_plan(_desc(**kw))
@@ -87,16 +90,30 @@ def test_plan_and_workspace_sizes():
     assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
     ws = vs.vs_attention_workspace_bytes(_desc())
     assert ws >= 4 * plan.num_splits * 448 * 130 * 4
-    # many short units: eight waves, rows split over two workgroups, no key split, no combine
+    assert plan.schedule == vs.VS_SCHED_LOOP
+    # many units: pipelined kernel, eight waves, rows split over two workgroups, no key split, no combine
     big = _desc(B=28, stride_seq=4 * 1800 * 128)
     rc, pb = vs.vs_attention_plan(big)
+    assert pb.schedule == vs.VS_SCHED_PIPELINED
     assert pb.rows_per_wave == 1 and pb.waves_per_group == 8 and pb.row_groups == 2
     assert pb.num_splits == 1 and pb.workgroups == 224 and pb.combine == 0
-    # many long units: two row blocks per wave and key splits that fill the CUs once
+    assert vs.vs_attention_workspace_bytes(big) == 0
     long_ = _desc(B=28, max_prefix_len=6684, capacity=6800, stride_seq=4 * 6800 * 128, stride_head=6800 * 128)
     rc, pl = vs.vs_attention_plan(long_)
-    assert pl.rows_per_wave == 2 and pl.waves_per_group == 8 and pl.row_groups == 1
-    assert pl.num_splits == 2 and pl.workgroups == 224 and pl.combine == 1
+    assert pl.schedule == vs.VS_SCHED_PIPELINED and pl.row_groups == 2 and pl.num_splits == 1 and pl.workgroups == 224
+    # fewer units than CUs: key splits fill the machine
+    mid = _desc(B=16, max_prefix_len=8192, capacity=8300, stride_seq=4 * 8300 * 128, stride_head=8300 * 128)
+    rc, pm5 = vs.vs_attention_plan(mid)
+    assert pm5.schedule == vs.VS_SCHED_PIPELINED and pm5.num_splits == 2 and pm5.workgroups == 256 and pm5.combine == 1
+    # few row blocks per unit (MHA): four waves
+    mha = _desc(B=32, Hq=32, Hkv=32, max_prefix_len=3136, capacity=3300, stride_seq=32 * 3300 * 128, stride_head=3300 * 128)
+    rc, pm2 = vs.vs_attention_plan(mha)
+    assert pm2.schedule == vs.VS_SCHED_PIPELINED and pm2.waves_per_group == 4 and pm2.row_groups == 1 and pm2.num_splits == 1
+    # two row blocks per wave exist in the straight loop only
+    rc, p2 = vs.vs_attention_plan(_desc(B=28, stride_seq=4 * 1800 * 128, rows_per_wave=2))
+    assert p2.schedule == vs.VS_SCHED_LOOP and p2.rows_per_wave == 2 and p2.waves_per_group == 8 and p2.num_splits == 2
+    rc, pf = vs.vs_attention_plan(_desc(schedule=vs.VS_SCHED_PIPELINED))
+    assert pf.schedule == vs.VS_SCHED_PIPELINED and pf.waves_per_group == 8 and pf.num_splits * pf.keys_per_split >= 1756
     # explicit knobs
     rc, plan1 = vs.vs_attention_plan(_desc(num_splits=1))
     assert plan1.num_splits == 1 and plan1.combine == 0 and vs.vs_attention_workspace_bytes(_desc(num_splits=1)) == 0

@@ -66,6 +66,12 @@ def test_full_size_single_sequence(gu, oracle_mod, name):
     for rpw in (1, 2):
         for nw in (1, 2, 4, 8):
             _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=3, rows_per_wave=rpw, waves_per_group=nw)
+    # the software-pipelined schedule: both wave counts, no split / few / many splits
+    for nw in (4, 8):
+        for sp in (1, 3, 0):
+            got_p, _, dp = _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=sp, waves_per_group=nw,
+                                          schedule=vs.VS_SCHED_PIPELINED)
+            assert dp.plan().schedule == vs.VS_SCHED_PIPELINED
     _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
 
 
@@ -76,16 +82,22 @@ def test_c5_ragged_paged_batch(gu, oracle_mod):
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=4)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=3, rows_per_wave=2, waves_per_group=8)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=2, rows_per_wave=1, waves_per_group=4)
+    for nw, sp in ((8, 1), (8, 2), (4, 5)):   # paged copies in the pipelined kernel
+        _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=sp, waves_per_group=nw, schedule=vs.VS_SCHED_PIPELINED)
 
 
 def test_layers_folded_into_batch(gu, oracle_mod):
     """The bench's roofline launch: the layers of one C3 step as independent batch entries."""
     cfg = dataclasses.replace(gen.CONFIGS["C3"], B=4, prefix=[1696] * 4)
     inp = gen.attention_inputs(cfg, 26)
-    _run_and_check(gu, oracle_mod, inp)
-    # the launch shapes the planner picks for 28 layers of short / long sequences
-    _run_and_check(gu, oracle_mod, inp, num_splits=1, rows_per_wave=1, waves_per_group=8)
-    _run_and_check(gu, oracle_mod, inp, num_splits=2, rows_per_wave=2, waves_per_group=8)
+    ref = oracle_mod.tree_attention(inp, threads=8)
+    _run_and_check(gu, oracle_mod, inp, ref=ref)
+    # the launch shape the planner picks for 28 layers: pipelined, eight waves, rows split over
+    # two workgroups, no key split
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=1, waves_per_group=8, schedule=vs.VS_SCHED_PIPELINED)
+    # and the straight-loop alternatives
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=1, rows_per_wave=1, waves_per_group=8, schedule=vs.VS_SCHED_LOOP)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=2, rows_per_wave=2, waves_per_group=8)
 
 
 # ---------------------------------------------------------------- fuzz over shapes
@@ -116,6 +128,7 @@ def test_fuzz_shapes(gu, oracle_mod, d, g, hkv, paged, T, S, splits, B, k):
     ref = oracle_mod.tree_attention(inp, threads=4)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits, rows_per_wave=1 + k % 2, waves_per_group=[8, 1, 4, 2][k % 4])
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits, waves_per_group=[4, 8][k % 2], schedule=vs.VS_SCHED_PIPELINED)
     _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
 
 
@@ -135,6 +148,7 @@ def test_tree_dominated_no_prefix(gu, oracle_mod):
         cfg = gen.Config("nopre", 2, g, 1, 128, T, 6, 4, 100, 0.5, 1, "bf16", prefix=[0, 0])
         inp = gen.attention_inputs(cfg, 40 + T)
         _run_and_check(gu, oracle_mod, inp)
+        _run_and_check(gu, oracle_mod, inp, schedule=vs.VS_SCHED_PIPELINED)
         _run_and_check(gu, oracle_mod, inp, impl=vs.VS_IMPL_GENERIC)
 
 
@@ -148,8 +162,9 @@ def test_mask_from_mask_build_equals_internal(gu, oracle_mod):
     assert np.array_equal(a, b)
 
 
-@pytest.mark.parametrize("impl", [vs.VS_IMPL_MFMA, vs.VS_IMPL_GENERIC])
-def test_needles(gu, oracle_mod, impl):
+@pytest.mark.parametrize("impl,sched", [(vs.VS_IMPL_MFMA, vs.VS_SCHED_LOOP), (vs.VS_IMPL_MFMA, vs.VS_SCHED_PIPELINED),
+                                        (vs.VS_IMPL_GENERIC, 0)])
+def test_needles(gu, oracle_mod, impl, sched):
     """A huge key on a NON-ancestor tree slot must not move a node's output; the same key
     on an ancestor slot must pull the output to that slot's value."""
     S, T = 300, 24
@@ -174,10 +189,10 @@ def test_needles(gu, oracle_mod, impl):
         return inp
 
     inp = planted(non_anc[0], 100.0)
-    got = gu.DeviceAttn(inp, impl=impl).run()
+    got = gu.DeviceAttn(inp, impl=impl, schedule=sched).run()
     gu.check_close(got[0, node, head], ref_base[0, node, head], *TIGHT_LONG, what="non-ancestor needle leaked")
     inp = planted(anc[1], 100.0)
-    got = gu.DeviceAttn(inp, impl=impl).run()
+    got = gu.DeviceAttn(inp, impl=impl, schedule=sched).run()
     ref = oracle_mod.tree_attention(inp)
     assert abs(ref[0, node, head, 0] - 100.0) < 1.0
     gu.check_close(got[0, node, head], ref[0, node, head], 0.5, 1e-2, what="ancestor needle")
@@ -235,6 +250,9 @@ def test_paged_equals_contiguous_bitwise(gu, oracle_mod):
                           cap=cap, scale=inp.scale, q_bits=inp.q_bits, k_bits=kb, v_bits=vb)
     cont = gu.DeviceAttn(inp2, num_splits=2).run()
     assert np.array_equal(paged, cont)
+    # the pipelined kernel: paged copies take the general path, contiguous ones the fast path
+    kw = dict(num_splits=2, waves_per_group=8, schedule=vs.VS_SCHED_PIPELINED)
+    assert np.array_equal(gu.DeviceAttn(inp, **kw).run(), gu.DeviceAttn(inp2, **kw).run())
 
 
 def test_deterministic_and_untouched_guards(gu):
@@ -253,6 +271,7 @@ def test_max_prefix_bound_larger_than_actual(gu, oracle_mod):
     cfg = dataclasses.replace(gen.CONFIGS["C3"], prefix=[130])
     inp = gen.attention_inputs(cfg, 46, extra_cap=4000)
     _run_and_check(gu, oracle_mod, inp, max_prefix_len=3000, num_splits=9)
+    _run_and_check(gu, oracle_mod, inp, max_prefix_len=3000, num_splits=9, schedule=vs.VS_SCHED_PIPELINED)
 
 
 # ---------------------------------------------------------------- data-dependent errors
@@ -264,8 +283,8 @@ def test_status_reports_bad_inputs_without_faulting(gu):
     inp.parent[1] = [-1, 0, 2, 1, 0, 0]            # parent[2] = 2 is not < 2
     inp.prefix_len[2] = 10 ** 6                    # beyond the cache
     inp.block_table[3, 0] = 10 ** 7                # outside the pool
-    for impl in (vs.VS_IMPL_MFMA, vs.VS_IMPL_GENERIC):
-        da = gu.DeviceAttn(inp, impl=impl, max_prefix_len=60)
+    for impl, sched in ((vs.VS_IMPL_MFMA, vs.VS_SCHED_LOOP), (vs.VS_IMPL_MFMA, vs.VS_SCHED_PIPELINED), (vs.VS_IMPL_GENERIC, 0)):
+        da = gu.DeviceAttn(inp, impl=impl, max_prefix_len=60, schedule=sched)
         da.run()
         st = da.status.cpu().numpy()
         assert list(st) == [0, 2, 3, 4], st
