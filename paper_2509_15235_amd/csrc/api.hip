@@ -141,15 +141,24 @@ Plan make_plan(const vs_attn_desc* d) {
     pl.row_groups = (need + pl.waves - 1) / pl.waves;
     const int units = units0 * pl.row_groups;
     if (splits <= 0) {
-        // large: fill the CUs once; small: ~1.5 workgroups per CU, at least two loop
-        // iterations (128 keys) per split
-        splits = big ? 256 / units : (384 + units / 2) / units;
+        // large: fill the CUs once. Small launches are latency-bound: workgroup dispatch
+        // (about 30 ns each) and the combine grow with the split count, the loop with the
+        // keys per split; measured optima were 4 iterations of 64 keys per split for short
+        // sequences and 8 for long ones, with at most ~1.5 workgroups per CU.
+        if (big) {
+            splits = 256 / units;
+        } else {
+            const int iters = tiles <= 32 ? 4 : (tiles <= 64 ? 5 : 8);
+            splits = (tiles + iters - 1) / iters;
+            const int cap = (384 + units / 2) / units;
+            if (splits > cap) splits = cap;
+        }
         const int max_splits = (tiles + 1) / 2;
         if (splits > max_splits) splits = max_splits;
     }
     if (splits < 1) splits = 1;
     if (splits > tiles) splits = tiles;
-    if (splits > 64) splits = 64; // the combine kernel stages at most 64 splits
+    if (splits > 64) splits = 64; // more splits than this only add partial-result traffic
     const int tiles_per_split = (tiles + splits - 1) / splits;
     pl.keys_per_split = tiles_per_split * kIterKeys;
     pl.num_splits = (tiles + tiles_per_split - 1) / tiles_per_split;

@@ -104,6 +104,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
 
     // With caller-supplied masks the tree was checked by the mask builder (which zeroes the
     // masks of a malformed tree); otherwise check it here.
+    const int32_t S = p.prefix_len[b]; // requested before the tree is read: one latency, not two
     int32_t tree_code = VS_STATUS_OK;
     if (p.tree_mask) {
         if (tid == 0) sflag = 0;
@@ -111,7 +112,6 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     } else {
         tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
     }
-    const int32_t S = p.prefix_len[b];
     const bool s_ok = prefix_ok(p, S);
     if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
     if (tree_code != VS_STATUS_OK || !s_ok) return;
@@ -475,55 +475,67 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
 // Merges the key splits: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s per query row.
 // One wave per (sequence, KV head, 32-row block, 32-channel block); lanes map to the
 // partials exactly as the accumulator registers did, the result is transposed through LDS
-// so that the bf16 rows leave as 16-byte stores. A sequence whose prefix length is out of
-// range is skipped; a malformed tree (reported by the main kernel) leaves unspecified output.
-constexpr int kCombineMaxSplits = 64; // (max, sum) pairs staged in LDS: 64 splits x 32 rows
+// so that the bf16 rows leave as 16-byte stores. The kernel is pure latency, so the prefix
+// length, every split's (max, sum) and every split's partials are requested back to back
+// before anything is waited for (splits past the sequence's end hold stale workspace
+// bytes; they are loaded but never used). A sequence whose prefix length is out of range
+// is skipped; a malformed tree (reported by the main kernel) leaves unspecified output.
+constexpr int kCombineBatch = 16; // splits whose partials are in flight together
 template <int D>
 __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p) {
     constexpr int DB = D / 32;
-    __shared__ f32x2 sml[kCombineMaxSplits * kRowBlock];
     __shared__ __attribute__((aligned(16))) uint16_t so[kRowBlock][32 + 8];
     const int unit = blockIdx.y;
     const int b = unit / p.Hkv, kvh = unit % p.Hkv;
     const int rbk = blockIdx.x / DB, db = blockIdx.x % DB;
     const int lane = threadIdx.x, col = lane & 31, half = lane >> 5;
     const int32_t S = p.prefix_len[b];
-    if (!prefix_ok(p, S)) return;
-    const int nk = S + p.T;
-    const int nsplit = min(p.num_splits, (nk + p.keys_per_split - 1) / p.keys_per_split);
+    const f32x2* gml = (const f32x2*)p.part_ml + ml_block(p, unit, 0, rbk) + col; // + s * kRowBlock
+    const int64_t blk0 = part_block(p, unit, 0, rbk);
+    const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
+    const float* po0 = p.part_o + blk0 * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
 
-    // stage every split's (max, sum) of the 32 rows: contiguous in the workspace
-    const f32x2* gml = (const f32x2*)p.part_ml + ml_block(p, unit, 0, rbk);
-    for (int i = lane; i < nsplit * kRowBlock; i += kWave) sml[i] = gml[i];
-    __syncthreads();
-    float M = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, sml[s * kRowBlock + col][0]);
-
-    float den = 0.f;
+    float den = 0.f, M = -INFINITY;
     f32x4 num[4];
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) num[q4] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int64_t blk0 = part_block(p, unit, 0, rbk);
-    const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
-    for (int s0 = 0; s0 < nsplit; s0 += 4) {
-        f32x4 o[4][4];
+    int nsplit = 0;
+    for (int s0 = 0; s0 < p.num_splits; s0 += kCombineBatch) {
+        f32x2 ml[kCombineBatch];
+        f32x4 o[kCombineBatch][4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int s = min(s0 + u, nsplit - 1); // past the end: re-read the last split, weight 0
-            const float* po = p.part_o + (blk0 + s * blk_stride) * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
+        for (int u = 0; u < kCombineBatch; ++u)
+            if (s0 + u < p.num_splits) ml[u] = __builtin_nontemporal_load(gml + (s0 + u) * kRowBlock);
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) o[u][q4] = *(const f32x4*)(po + q4 * 256);
+        for (int u = 0; u < kCombineBatch; ++u)
+            if (s0 + u < p.num_splits) {
+                const float* po = po0 + (s0 + u) * blk_stride * (kRowBlock * D);
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) o[u][q4] = __builtin_nontemporal_load((const f32x4*)(po + q4 * 256));
+            }
+        if (s0 == 0) {
+            if (!prefix_ok(p, S)) return;
+            nsplit = min(p.num_splits, (S + p.T + p.keys_per_split - 1) / p.keys_per_split);
         }
+        // this batch's maximum joins the running one; what was summed so far is rescaled
+        float Mb = M;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const f32x2 ml = sml[min(s0 + u, nsplit - 1) * kRowBlock + col];
-            // a split that saw no visible key for the row has max -inf, sum 0 and zero partials
-            const bool live = (s0 + u < nsplit) && (ml[0] != -INFINITY);
-            const float w = live ? __builtin_amdgcn_exp2f(ml[0] - M) : 0.f;
-            den += w * ml[1];
+        for (int u = 0; u < kCombineBatch; ++u)
+            if (s0 + u < nsplit) Mb = fmaxf(Mb, ml[u][0]);
+        const float resc = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mb); // nothing summed yet: 0
+        den *= resc;
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * o[u][q4];
-        }
+        for (int q4 = 0; q4 < 4; ++q4) num[q4] *= resc;
+        M = Mb;
+#pragma unroll
+        for (int u = 0; u < kCombineBatch; ++u)
+            if (s0 + u < nsplit) { // uniform
+                // a split that saw no visible key for the row has max -inf, sum 0 and zero partials
+                const float w = (ml[u][0] != -INFINITY) ? __builtin_amdgcn_exp2f(ml[u][0] - M) : 0.f;
+                den += w * ml[u][1];
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * o[u][q4];
+            }
     }
     const float inv = 1.f / den;
 #pragma unroll

@@ -66,6 +66,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     const int kvh = rest % p.Hkv;
     const int b = rest / p.Hkv;
 
+    const int32_t S = p.prefix_len[b]; // requested before the tree is read: one latency, not two
     int32_t tree_code = VS_STATUS_OK;
     if (p.tree_mask) {
         if (tid == 0) sflag = 0;
@@ -73,7 +74,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     } else {
         tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
     }
-    const int32_t S = p.prefix_len[b];
     const bool s_ok = prefix_ok(p, S);
     if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
     if (tree_code != VS_STATUS_OK || !s_ok) return;
