@@ -26,6 +26,7 @@ STREAM_TOKENS = 6
 STREAM_PLANT = 7
 STREAM_PREFIX = 8
 STREAM_BLOCKS = 9
+STREAM_PATH = 10
 
 
 def rng(seed: int, stream: int, sub: int = 0) -> np.random.Generator:
@@ -358,3 +359,20 @@ def accept_inputs(cfg: Config, seed: int, parent: Optional[np.ndarray] = None,
         lg[b] = logits_with_plants(rng(seed, STREAM_LOGITS, b), rng(seed, STREAM_PLANT, b),
                                    parent[b], tok[b], cfg.V, cfg.pi)
     return AcceptInputs(cfg, parent[:nb], tok, lg)
+
+
+def random_accept_path(g: np.random.Generator, parent: np.ndarray, full: bool = False):
+    """A root-to-node path of one tree, as tree_accept reports it: (path int32[T] padded with
+    -1, accepted_len). The end node is drawn uniformly (the deepest node of lowest index if
+    `full`)."""
+    T = len(parent)
+    depth = np.zeros(T, dtype=np.int32)
+    for i in range(1, T):
+        depth[i] = depth[parent[i]] + 1
+    end = int(np.argmax(depth)) if full else int(g.integers(0, T))
+    path = np.full(T, -1, dtype=np.int32)
+    j = end
+    while j != -1:
+        path[depth[j]] = j
+        j = int(parent[j])
+    return path, int(depth[end])

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-OK, BAD_ROOT, BAD_PARENT, BAD_SIZE = 0, 1, 2, 3
+OK, BAD_ROOT, BAD_PARENT, BAD_SIZE, BAD_PATH = 0, 1, 2, 3, 4
 
 
 def build(force: bool = False) -> str:
@@ -53,6 +53,11 @@ def _load():
         lib.oracle_row_argmax.restype = ctypes.c_int64
         lib.oracle_tree_accept.argtypes = [i32p, i32p, i32p, ctypes.c_int32, i32p, i32p, i32p]
         lib.oracle_tree_accept.restype = ctypes.c_int
+        lib.oracle_kv_commit.argtypes = [
+            ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+            i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int32,
+            ctypes.c_int64, i32p]
+        lib.oracle_kv_commit.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -180,3 +185,28 @@ def tree_accept(logits, draft, parent):
         if rc != OK:
             raise ValueError(f"oracle_tree_accept failed with code {rc}")
     return amax, alen, path, bonus
+
+
+def kv_commit_seq(cache, S, path, accepted_len, *, block_table=None, block_size=16):
+    """Moves the accepted path's rows of ONE sequence inside `cache` IN PLACE and returns
+    (rc, new_prefix). Contiguous: cache [Hkv, cap, d]; paged: cache [n_blocks, Hkv, block_size, d]
+    (the whole pool) with that sequence's block_table row. Any dtype; rows move as bytes."""
+    assert cache.flags["C_CONTIGUOUS"]
+    path = _i32(path)
+    T = len(path)
+    d = cache.shape[-1]
+    if block_table is None:
+        Hkv, cap = cache.shape[0], cache.shape[1]
+        assert S + T <= cap
+        paged, sh, st, sb = 0, cap * d, d, 0
+        bt = np.zeros(1, dtype=np.int32)
+    else:
+        bt = _i32(block_table)
+        Hkv = cache.shape[1]
+        assert cache.shape[2] == block_size
+        paged, sh, st, sb = 1, block_size * d, d, Hkv * block_size * d
+    newp = np.zeros(1, dtype=np.int32)
+    rc = _load().oracle_kv_commit(cache.ctypes.data_as(ctypes.c_void_p), cache.dtype.itemsize, Hkv, d, int(S), T,
+                                  _p(path, ctypes.c_int32), int(accepted_len), paged, sh, st,
+                                  _p(bt, ctypes.c_int32), block_size, sb, _p(newp, ctypes.c_int32))
+    return int(rc), int(newp[0])

@@ -26,16 +26,23 @@
  *   oracle_tree_accept  brute-force enumeration of root-to-leaf paths (a
  *       separate implementation in another language), forced full/zero
  *       acceptance, structural invariants of the returned path.
+ *   oracle_kv_commit  an out-of-place gather from a pristine copy of the cache
+ *       (numpy fancy indexing), identity on a chain path, untouched bytes
+ *       outside the destination rows, and the closed loop: attention over the
+ *       committed cache equals attention over the accepted tokens' rows taken
+ *       from the original cache.
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
+#include <string.h>
 
 enum {
     ORACLE_OK = 0,
     ORACLE_BAD_ROOT = 1,   /* parent[0] != -1 */
     ORACLE_BAD_PARENT = 2, /* parent[i] outside [0, i) for some i >= 1 */
-    ORACLE_BAD_SIZE = 3
+    ORACLE_BAD_SIZE = 3,
+    ORACLE_BAD_PATH = 4    /* accepted path is not root, then strictly increasing node ids */
 };
 
 /* Section 3.1, "draft tree": node 0 is the root (the last committed token), every
@@ -192,5 +199,41 @@ int oracle_tree_accept(const int32_t* amax, const int32_t* draft, const int32_t*
     for (int32_t k = 0; k < T; ++k) path[k] = -1;
     for (int32_t j = best; j != -1; j = parent[j]) path[depth[j]] = j;
     *bonus = amax[best];
+    return ORACLE_OK;
+}
+
+/* Commit of the accepted path into a pre-allocated KV cache (Section 3.1: the draft
+ * tokens after the first rejected one are discarded; Appendix A: the cache is
+ * allocated once, so keeping the accepted tokens means moving their rows).
+ *
+ * Before the call the cache of one sequence holds S prefix tokens and the T tree
+ * nodes' rows at logical slots S .. S+T-1 (node i at S+i). path[0..accepted_len]
+ * is the accepted root-to-node path (path[0] = 0, node ids strictly increasing,
+ * as oracle_tree_accept returns it). After the call slot S+k holds the row of node
+ * path[k] for k = 0 .. accepted_len, i.e. the sequence's context is the old prefix
+ * plus the accepted tokens in order, and *new_prefix = S + accepted_len + 1.
+ * Rows are moved as bytes, one k after the other in ascending order; since
+ * path[k] >= k no source row is overwritten before it is read. Slots above
+ * S + accepted_len keep whatever they held.
+ *
+ * `cache` is one tensor (K or V) of one layer and one sequence (contiguous) or the
+ * block pool (paged); offsets are in elements of elem_bytes bytes. */
+int oracle_kv_commit(unsigned char* cache, int32_t elem_bytes, int32_t Hkv, int32_t d, int32_t S,
+                     int32_t T, const int32_t* path, int32_t accepted_len, int32_t paged,
+                     int64_t stride_head, int64_t stride_tok, const int32_t* block_table,
+                     int32_t block_size, int64_t stride_block, int32_t* new_prefix) {
+    if (T < 1 || T > 64 || S < 0) return ORACLE_BAD_SIZE;
+    if (accepted_len < 0 || accepted_len >= T || path[0] != 0) return ORACLE_BAD_PATH;
+    for (int32_t k = 1; k <= accepted_len; ++k)
+        if (path[k] <= path[k - 1] || path[k] >= T) return ORACLE_BAD_PATH;
+    oracle_kv_layout L = {paged, stride_head, stride_tok, block_table, block_size, stride_block};
+    const size_t row_bytes = (size_t)d * (size_t)elem_bytes;
+    for (int32_t kvh = 0; kvh < Hkv; ++kvh)
+        for (int32_t k = 1; k <= accepted_len; ++k) {
+            const int64_t src = token_offset(&L, kvh, S + path[k]);
+            const int64_t dst = token_offset(&L, kvh, S + k);
+            if (src != dst) memmove(cache + dst * elem_bytes, cache + src * elem_bytes, row_bytes);
+        }
+    *new_prefix = S + accepted_len + 1;
     return ORACLE_OK;
 }
