@@ -12,6 +12,8 @@
  *                             of the T tree queries over prefix + visible tree keys
  *   vs_tree_accept            vocab-wide argmax per node, longest accepted path and
  *                             bonus token (Section 3.1 at temperature 0)
+ *   vs_tree_kv_commit         keeps the accepted path's K/V rows, in order, behind the
+ *                             prefix of the pre-allocated cache (Section 3.1, Appendix A)
  *
  * Conventions
  *   - C ABI, no exceptions cross it. Every function returns an int32 vs_error
@@ -60,7 +62,8 @@ typedef enum vs_status {
     VS_STATUS_BAD_ROOT = 1,   /* parent[0] != -1 */
     VS_STATUS_BAD_PARENT = 2, /* some parent[i], i >= 1, outside [0, i) */
     VS_STATUS_BAD_PREFIX = 3, /* prefix_len < 0, > max_prefix_len, or prefix_len + T beyond the cache */
-    VS_STATUS_BAD_BLOCK = 4   /* a block-table entry in use lies outside [0, num_blocks) */
+    VS_STATUS_BAD_BLOCK = 4,  /* a block-table entry in use lies outside [0, num_blocks) */
+    VS_STATUS_BAD_PATH = 5    /* accepted_len outside [0, T) or path not 0 followed by increasing node ids */
 } vs_status;
 
 typedef enum vs_dtype { VS_BF16 = 0, VS_F32 = 1 } vs_dtype;
@@ -200,6 +203,49 @@ int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V,
                        int32_t* accepted_len, int32_t* path, int32_t* bonus_token,
                        int32_t* row_argmax, int32_t* status, void* workspace,
                        size_t workspace_bytes, void* stream);
+
+/*
+ * KV caches of one or more layers that share a layout (host struct, read during the call).
+ * Element offset of (layer l, sequence b, KV head kv, logical token t, channel c) in k_cache
+ * and in v_cache: l*stride_layer + the offset vs_attn_desc documents. Every stride times
+ * the element size, and d times the element size, must be a multiple of 16 bytes; the
+ * cache pointers must be 16-byte aligned.
+ */
+typedef struct vs_kv_desc {
+    int32_t B;              /* sequences */
+    int32_t T;              /* tree nodes per sequence incl. root, 1..64 */
+    int32_t Hkv;
+    int32_t d;
+    int32_t dtype;          /* vs_dtype of the caches */
+    int32_t num_layers;     /* >= 1 */
+    int64_t stride_layer;   /* elements between consecutive layers' caches */
+    int32_t paged, block_size, max_blocks, num_blocks;
+    int64_t capacity, stride_seq, stride_block, stride_head, stride_tok;
+    const int32_t* block_table; /* paged: device [B, max_blocks], shared by all layers */
+} vs_kv_desc;
+
+/*
+ * Commit of the accepted path (Section 3.1: draft tokens after the first rejected one are
+ * discarded; Appendix A: the cache is pre-allocated, so the accepted tokens' rows move).
+ * Before the call sequence b's cache holds prefix_len[b] context tokens and node i's K/V at
+ * logical slot prefix_len[b] + i. For every layer and KV head, the K and V rows of node
+ * path[b][k] move to slot prefix_len[b] + k, k = 1 .. accepted_len[b] (bit-exact copies;
+ * slots above prefix_len[b] + accepted_len[b] keep what they held), and
+ * new_prefix_len[b] = prefix_len[b] + accepted_len[b] + 1: the context of the next step is the
+ * old prefix, the root and the accepted draft tokens in order. The bonus token is not in the
+ * cache yet; it is the next step's root.
+ *   k_cache, v_cache        in/out, layout per desc
+ *   prefix_len     [B] int32     in
+ *   path           [B,T] int32   in, as vs_tree_accept writes it
+ *   accepted_len   [B] int32     in
+ *   new_prefix_len [B] int32     out; must not overlap prefix_len
+ *   status         [B] int32     out, optional
+ * A sequence with a malformed path, a prefix length beyond the cache or a block id outside
+ * the pool is reported in status, keeps its cache and gets new_prefix_len[b] = prefix_len[b].
+ */
+int32_t vs_tree_kv_commit(const vs_kv_desc* desc, void* k_cache, void* v_cache, const int32_t* prefix_len,
+                          const int32_t* path, const int32_t* accepted_len, int32_t* new_prefix_len,
+                          int32_t* status, void* stream);
 
 #ifdef __cplusplus
 }

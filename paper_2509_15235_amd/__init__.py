@@ -7,9 +7,9 @@ There is no CPU fallback: if the shared library is missing, importing the bindin
 functions raises.
 """
 from .binding import (  # noqa: F401
-    AttnDesc, AttnPlan, VSError, lib, lib_path,
+    AttnDesc, AttnPlan, KVDesc, VSError, lib, lib_path,
     VS_BF16, VS_F32, VS_IMPL_AUTO, VS_IMPL_GENERIC, VS_IMPL_MFMA, VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED,
     vs_version, vs_strerror, vs_status_string, vs_tree_validate_host, vs_tree_mask_build,
     vs_attention_plan, vs_attention_workspace_bytes, vs_tree_verify_attention,
-    vs_accept_workspace_bytes, vs_tree_accept, EXPORTED_SYMBOLS,
+    vs_accept_workspace_bytes, vs_tree_accept, vs_tree_kv_commit, EXPORTED_SYMBOLS,
 )

@@ -14,7 +14,7 @@ VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED = 0, 1, 2
 EXPORTED_SYMBOLS = [
     "vs_version", "vs_strerror", "vs_status_string", "vs_tree_validate_host", "vs_tree_mask_build",
     "vs_attention_plan", "vs_attention_workspace_bytes", "vs_tree_verify_attention",
-    "vs_accept_workspace_bytes", "vs_tree_accept",
+    "vs_accept_workspace_bytes", "vs_tree_accept", "vs_tree_kv_commit",
 ]
 
 
@@ -34,6 +34,17 @@ class AttnDesc(ctypes.Structure):
         ("stride_tok", ctypes.c_int64), ("block_table", ctypes.c_void_p), ("impl", ctypes.c_int32),
         ("num_splits", ctypes.c_int32), ("rows_per_wave", ctypes.c_int32), ("waves_per_group", ctypes.c_int32),
         ("schedule", ctypes.c_int32),
+    ]
+
+
+class KVDesc(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("num_layers", ctypes.c_int32), ("stride_layer", ctypes.c_int64),
+        ("paged", ctypes.c_int32), ("block_size", ctypes.c_int32), ("max_blocks", ctypes.c_int32),
+        ("num_blocks", ctypes.c_int32), ("capacity", ctypes.c_int64), ("stride_seq", ctypes.c_int64),
+        ("stride_block", ctypes.c_int64), ("stride_head", ctypes.c_int64), ("stride_tok", ctypes.c_int64),
+        ("block_table", ctypes.c_void_p),
     ]
 
 
@@ -82,6 +93,8 @@ def lib():
         L.vs_accept_workspace_bytes.restype = sz
         L.vs_tree_accept.argtypes = [vp, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vs_tree_accept.restype = i32
+        L.vs_tree_kv_commit.argtypes = [ctypes.POINTER(KVDesc), vp, vp, vp, vp, vp, vp, vp, vp]
+        L.vs_tree_kv_commit.restype = i32
         _lib = L
     return _lib
 
@@ -146,3 +159,9 @@ def vs_tree_accept(logits, ld_logits, V, draft_tokens, parent, B, T, accepted_le
     return lib().vs_tree_accept(_ptr(logits), ld_logits, V, _ptr(draft_tokens), _ptr(parent), B, T,
                                 _ptr(accepted_len), _ptr(path), _ptr(bonus_token), _ptr(row_argmax),
                                 _ptr(status), _ptr(workspace), workspace_bytes, _ptr(stream))
+
+
+def vs_tree_kv_commit(desc: KVDesc, k_cache, v_cache, prefix_len, path, accepted_len, new_prefix_len,
+                      status=None, stream=None) -> int:
+    return lib().vs_tree_kv_commit(ctypes.byref(desc), _ptr(k_cache), _ptr(v_cache), _ptr(prefix_len), _ptr(path),
+                                   _ptr(accepted_len), _ptr(new_prefix_len), _ptr(status), _ptr(stream))

@@ -203,6 +203,7 @@ const char* vs_status_string(int32_t code) {
     case VS_STATUS_BAD_PARENT: return "a parent index is outside [0, i)";
     case VS_STATUS_BAD_PREFIX: return "prefix_len outside the cache or the host bound";
     case VS_STATUS_BAD_BLOCK: return "a block-table entry is outside the pool";
+    case VS_STATUS_BAD_PATH: return "accepted path is not the root followed by increasing node ids";
     default: return "unknown status";
     }
 }
@@ -346,5 +347,58 @@ int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V, const 
     p.part_idx = (int32_t*)((char*)workspace + align_up(n * sizeof(float)));
     return launch_accept(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
 }
+
+int32_t vs_tree_kv_commit(const vs_kv_desc* d, void* k_cache, void* v_cache, const int32_t* prefix_len,
+                          const int32_t* path, const int32_t* accepted_len, int32_t* new_prefix_len,
+                          int32_t* status, void* stream) {
+    if (!d || !k_cache || !v_cache || !prefix_len || !path || !accepted_len || !new_prefix_len) return VS_ERR_NULL;
+    if (d->B < 1 || d->T < 1 || d->T > VS_MAX_TREE || d->Hkv < 1 || d->d < 1 || d->num_layers < 1) return VS_ERR_SHAPE;
+    if (d->dtype != VS_BF16 && d->dtype != VS_F32) return VS_ERR_DTYPE;
+    const int64_t eb = d->dtype == VS_BF16 ? 2 : 4;
+    if (d->stride_head < 0 || d->stride_tok < d->d || d->stride_layer < 0) return VS_ERR_LAYOUT;
+    if (d->paged) {
+        if (!is_pow2(d->block_size) || d->block_size < 16) return VS_ERR_LAYOUT;
+        if (d->max_blocks < 1 || d->num_blocks < 1 || d->stride_block < 0) return VS_ERR_LAYOUT;
+        if (!d->block_table) return VS_ERR_NULL;
+        if (d->T > (int64_t)d->max_blocks * d->block_size) return VS_ERR_LAYOUT;
+    } else {
+        if (d->stride_seq < 0 || d->capacity < d->T) return VS_ERR_LAYOUT;
+    }
+    // rows move in 16-byte pieces
+    if ((d->d * eb) % 16 || (d->stride_tok * eb) % 16 || (d->stride_head * eb) % 16 || (d->stride_layer * eb) % 16 ||
+        ((d->paged ? d->stride_block : d->stride_seq) * eb) % 16)
+        return VS_ERR_LAYOUT;
+    if (!aligned16(k_cache) || !aligned16(v_cache)) return VS_ERR_LAYOUT;
+    if (new_prefix_len == prefix_len) return VS_ERR_LAYOUT;
+    CommitParams p{};
+    p.k = k_cache;
+    p.v = v_cache;
+    p.prefix_len = prefix_len;
+    p.path = path;
+    p.accepted_len = accepted_len;
+    p.block_table = d->paged ? d->block_table : nullptr;
+    p.new_prefix_len = new_prefix_len;
+    p.status = status;
+    p.B = d->B;
+    p.T = d->T;
+    p.Hkv = d->Hkv;
+    p.chunks_per_row = (int32_t)(d->d * eb / 16);
+    p.items_per_seq = (int64_t)d->num_layers * 2 * d->Hkv * p.chunks_per_row;
+    p.paged = d->paged ? 1 : 0;
+    p.block_size = d->paged ? d->block_size : 1;
+    p.block_shift = 0;
+    while ((1 << p.block_shift) < p.block_size) ++p.block_shift;
+    p.max_blocks = d->max_blocks;
+    p.num_blocks = d->num_blocks;
+    p.capacity = d->capacity;
+    p.stride_layer_bytes = d->stride_layer * eb;
+    p.stride_seq_bytes = d->stride_seq * eb;
+    p.stride_block_bytes = d->stride_block * eb;
+    p.stride_head_bytes = d->stride_head * eb;
+    p.stride_tok_bytes = d->stride_tok * eb;
+    if ((p.items_per_seq + 255) / 256 > 0x7fffffffLL || d->B > 65535) return VS_ERR_SHAPE;
+    return launch_kv_commit(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
+}
+
 
 } // extern "C"

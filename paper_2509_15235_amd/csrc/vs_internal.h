@@ -63,6 +63,23 @@ struct AcceptParams {
     int32_t vec_ok;      // rows are 16-byte aligned → float4 loads
 };
 
+struct CommitParams {
+    void* k;
+    void* v;
+    const int32_t* prefix_len;
+    const int32_t* path;         // [B][T]
+    const int32_t* accepted_len; // [B]
+    const int32_t* block_table;  // paged only
+    int32_t* new_prefix_len;     // [B]
+    int32_t* status;             // may be null
+    int32_t B, T, Hkv;
+    int32_t chunks_per_row;      // 16-byte pieces per row of d elements
+    int64_t items_per_seq;       // layers * 2 * Hkv * chunks_per_row
+    int32_t paged, block_size, block_shift, max_blocks, num_blocks;
+    int64_t capacity;
+    int64_t stride_layer_bytes, stride_seq_bytes, stride_block_bytes, stride_head_bytes, stride_tok_bytes;
+};
+
 // Shared tree check: returns a vs_status for lane-parallel use is in the kernels; this is
 // the scalar form used on the host.
 inline int32_t validate_tree_host(const int32_t* parent, int32_t T) {
@@ -80,5 +97,6 @@ bool attention_pipe_supported(int rpw, int waves);
 hipError_t launch_attention_mfma_pipe(const AttnParams& p, int rpw, int waves, hipStream_t s);
 hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
+hipError_t launch_kv_commit(const CommitParams& p, hipStream_t s);
 
 } // namespace vs

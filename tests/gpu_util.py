@@ -127,3 +127,46 @@ def run_accept(logits: np.ndarray, tokens: np.ndarray, parent: np.ndarray, ld=No
     assert rc == 0, vs.vs_strerror(rc)
     torch.cuda.synchronize()
     return (amax.cpu().numpy(), alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy(), status.cpu().numpy())
+
+
+class DeviceCommit:
+    """Device copies of L layers of K/V caches (stacked along a leading layer axis) plus the
+    descriptor of vs_tree_kv_commit. `k_layers` / `v_layers`: numpy [L, ...one layer's cache...]
+    of uint16 (bf16 storage) or float32."""
+
+    def __init__(self, cfg, k_layers, v_layers, prefix_len, path, accepted_len, block_table=None):
+        bf = k_layers.dtype == np.uint16
+        self.k = dev_bf16(k_layers) if bf else dev(k_layers)
+        self.v = dev_bf16(v_layers) if bf else dev(v_layers)
+        self.bf = bf
+        B, T = path.shape
+        self.prefix = dev(prefix_len.astype(np.int32))
+        self.path = dev(path.astype(np.int32))
+        self.alen = dev(accepted_len.astype(np.int32))
+        self.newp = torch.full((B,), -7, device="cuda", dtype=torch.int32)
+        self.status = torch.full((B,), -99, device="cuda", dtype=torch.int32)
+        d = vs.KVDesc()
+        d.B, d.T, d.Hkv, d.d = B, T, cfg.Hkv, cfg.d
+        d.dtype = vs.VS_BF16 if bf else vs.VS_F32
+        d.num_layers = k_layers.shape[0]
+        d.stride_layer = int(np.prod(k_layers.shape[1:]))
+        if block_table is None:
+            cap = k_layers.shape[3]
+            d.paged, d.capacity = 0, cap
+            d.stride_seq, d.stride_head, d.stride_tok = cfg.Hkv * cap * cfg.d, cap * cfg.d, cfg.d
+            self.table = None
+        else:
+            self.table = dev(block_table.astype(np.int32))
+            d.paged, d.block_size = 1, cfg.block_size
+            d.max_blocks, d.num_blocks = block_table.shape[1], k_layers.shape[1]
+            d.stride_block, d.stride_head, d.stride_tok = cfg.Hkv * cfg.block_size * cfg.d, cfg.block_size * cfg.d, cfg.d
+            d.block_table = self.table.data_ptr()
+        self.desc = d
+
+    def run(self):
+        rc = vs.vs_tree_kv_commit(self.desc, self.k, self.v, self.prefix, self.path, self.alen, self.newp, self.status,
+                                  stream_ptr())
+        assert rc == 0, vs.vs_strerror(rc)
+        torch.cuda.synchronize()
+        host = (lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)) if self.bf else (lambda t: t.cpu().numpy())
+        return host(self.k), host(self.v), self.newp.cpu().numpy(), self.status.cpu().numpy()

@@ -146,3 +146,29 @@ def test_calls_reject_bad_arguments_before_any_launch():
     assert vs.vs_tree_accept(good, 9, 10, good, good, 1, 4, good, good, good, None, None, good, 1 << 20) == -2
     assert vs.vs_tree_accept(good, 10, 10, good, good, 1, 4, good, good, good, None, None, None, 0) == -4
     assert vs.vs_tree_accept(good, 10, 10, good, good, 1, 4, good, good, good, None, None, good, 8) == -4
+
+
+def test_kv_commit_rejects_bad_arguments_before_any_launch():
+    def kd(**kw):
+        d = vs.KVDesc(B=2, T=8, Hkv=2, d=64, dtype=vs.VS_BF16, num_layers=3, stride_layer=2 * 2 * 100 * 64,
+                      capacity=100, stride_seq=2 * 100 * 64, stride_head=100 * 64, stride_tok=64)
+        for k, v in kw.items():
+            setattr(d, k, v)
+        return d
+    g = 4096  # never dereferenced: every call below fails validation first
+    assert vs.vs_tree_kv_commit(kd(), None, g, g, g, g, g + 64) == -1
+    assert vs.vs_tree_kv_commit(kd(), g, g, g, g, g, None) == -1
+    assert vs.vs_tree_kv_commit(kd(T=0), g, g, g, g, g, g + 64) == -2
+    assert vs.vs_tree_kv_commit(kd(T=65), g, g, g, g, g, g + 64) == -2
+    assert vs.vs_tree_kv_commit(kd(num_layers=0), g, g, g, g, g, g + 64) == -2
+    assert vs.vs_tree_kv_commit(kd(dtype=3), g, g, g, g, g, g + 64) == -3
+    assert vs.vs_tree_kv_commit(kd(d=4), g, g, g, g, g, g + 64) == -6            # 8-byte rows
+    assert vs.vs_tree_kv_commit(kd(stride_tok=68), g, g, g, g, g, g + 64) == -6   # 136-byte row pitch
+    assert vs.vs_tree_kv_commit(kd(capacity=4), g, g, g, g, g, g + 64) == -6
+    assert vs.vs_tree_kv_commit(kd(), g + 2, g, g, g, g, g + 64) == -6            # misaligned cache
+    assert vs.vs_tree_kv_commit(kd(), g, g, g, g, g, g) == -6                     # new_prefix_len aliases prefix_len
+    assert vs.vs_tree_kv_commit(kd(paged=1, block_size=16, max_blocks=8, num_blocks=9, stride_block=2 * 16 * 64,
+                                   stride_head=16 * 64), g, g, g, g, g, g + 64) == -1   # no block table
+    assert vs.vs_tree_kv_commit(kd(paged=1, block_size=24, max_blocks=8, num_blocks=9, block_table=g), g, g, g, g, g,
+                                g + 64) == -6
+    assert "accepted path" in vs.vs_status_string(5)
