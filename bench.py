@@ -149,6 +149,13 @@ def main():
         check(vs.vs_tree_verify_attention(descL, st["q"], st["k"], st["v"], prefixL, parentL, maskL, st["out"],
                                           status, ws, ws_bytes, stream))
 
+    kvdesc = vs.KVDesc(B=1, T=T, Hkv=Hkv, d=d, dtype=vs.VS_BF16, num_layers=L, stride_layer=Hkv * cap * d, paged=0,
+                       capacity=cap, stride_seq=Hkv * cap * d, stride_head=cap * d, stride_tok=d)
+    new_prefix = torch.zeros((1,), device=dev, dtype=torch.int32)
+
+    def enqueue_commit(st, stream):
+        check(vs.vs_tree_kv_commit(kvdesc, st["k"], st["v"], prefix1, path, alen, new_prefix, status, stream))
+
     def enqueue_accept(st, stream):
         check(vs.vs_tree_accept(st["logits"], V, V, tokens, parent1, 1, T, alen, path, bonus, amax, status,
                                 aws, aws_bytes, stream))
@@ -169,8 +176,20 @@ def main():
     o_amax, o_alen, o_path, o_bonus = oracle.tree_accept(acc_h.logits, acc_h.tokens, acc_h.parent)
     accept_ok = bool((amax.cpu().numpy() == o_amax).all() and alen.item() == o_alen[0] and bonus.item() == o_bonus[0]
                      and (path.cpu().numpy() == o_path).all())
-    if not (err0 <= 2e-2 and accept_ok):
-        print(f"bench.py: parity check failed (attention max|err| {err0}, accept ok {accept_ok})", file=sys.stderr)
+    # commit of the accepted path: every layer of set 0 against the oracle, byte for byte
+    with torch.cuda.stream(stream):
+        enqueue_commit(sets[0], sp)
+    stream.synchronize()
+    commit_ok = int(new_prefix.item()) == S + int(o_alen[0]) + 1
+    for name, bits in (("k", "k_bits"), ("v", "v_bits")):
+        got = sets[0][name].view(torch.int16).cpu().numpy().view(np.uint16)                # [L,Hkv,cap,d]
+        for l in range(L):
+            want = getattr(host_layers[l], bits)[0].copy()
+            oracle.kv_commit_seq(want, S, o_path[0], int(o_alen[0]))
+            commit_ok = commit_ok and bool(np.array_equal(got[l], want))
+    if not (err0 <= 2e-2 and accept_ok and commit_ok):
+        print(f"bench.py: parity check failed (attention max|err| {err0}, accept ok {accept_ok}, commit ok {commit_ok})",
+              file=sys.stderr)
         sys.exit(4)
 
     # ---------------------------------------------------------------- runners (HIP graphs or eager)
@@ -218,6 +237,9 @@ def main():
 
     accept_runner = build_runner(enqueue_accept)
     ms_accept, _ = timed(accept_runner, max(args.steps, 50), max(args.warmup, 5))
+
+    commit_runner = build_runner(enqueue_commit)
+    ms_commit, _ = timed(commit_runner, max(args.steps, 50), max(args.warmup, 5))
 
     # a plain device copy of known size: the reference that scales rocprofv3's FETCH_SIZE /
     # WRITE_SIZE counters when HBM traffic of the kernels above is derived from a --pmc run
@@ -272,6 +294,10 @@ def main():
               "frac": round(argmax_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(ms_accept * 1e3, 2),
               "bytes": logit_bytes}
 
+    commit_bytes = 2 * 2 * L * Hkv * int(o_alen[0]) * d * eb                               # rows read + rows written, K and V
+    commit = {"bound": "latency", "us_per_launch": round(ms_commit * 1e3, 2), "accepted_len": int(o_alen[0]),
+              "bytes": commit_bytes, "note": "after the step (not part of it): moves accepted rows of all layers"}
+
     # ---------------------------------------------------------------- CPU baseline: the oracle, one full step
     cpu = None
     if not args.no_cpu_baseline:
@@ -292,8 +318,8 @@ def main():
         "config": {"workload": f"{cfg.name}: B=1 Hq={Hq} Hkv={Hkv} d={d} prefix={S} tree={T} nodes depth<={cfg.max_depth} "
                                f"layers={L} vocab={V}; step = mask_build + {L} x attention + accept",
                    "hip_graph": not args.no_graph, "buffer_sets": nsets},
-        "roofline": roofline, "per_layer_call": per_layer, "argmax": argmax, "cpu_baseline": cpu,
-        "parity": {"attention_max_abs_err_layer0": err0, "accept_bit_exact": accept_ok},
+        "roofline": roofline, "per_layer_call": per_layer, "argmax": argmax, "kv_commit": commit, "cpu_baseline": cpu,
+        "parity": {"attention_max_abs_err_layer0": err0, "accept_bit_exact": accept_ok, "commit_bit_exact": commit_ok},
     }
     print(json.dumps(line))
 
