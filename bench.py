@@ -226,8 +226,14 @@ def main():
     ms_step, ms_step_wall = timed(step_runner, args.steps, args.warmup)
     ms_step = max(ms_step, ms_step_wall) if args.no_graph else ms_step
 
-    folded_runner = build_runner(enqueue_folded)
-    ms_folded, _ = timed(folded_runner, max(args.steps, 50), max(args.warmup, 5))
+    # the roofline launch: one graph holds one folded call per buffer set, back to back, so that
+    # the event time per call is the kernel's duration and not the gap between graph launches
+    def enqueue_folded_all(_st, stream_):
+        for st in sets:
+            enqueue_folded(st, stream_)
+    folded_runner = build_runner(enqueue_folded_all)
+    ms_folded, _ = timed(folded_runner, max(args.steps // 4, 12), 3)
+    ms_folded /= nsets
 
     def enqueue_one_layer(st, stream_):
         check(vs.vs_tree_verify_attention(desc1, st["q"], st["k"], st["v"], prefix1, parent1, mask, st["out"],
