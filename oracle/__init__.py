@@ -53,6 +53,11 @@ def _load():
         lib.oracle_row_argmax.restype = ctypes.c_int64
         lib.oracle_tree_accept.argtypes = [i32p, i32p, i32p, ctypes.c_int32, i32p, i32p, i32p]
         lib.oracle_tree_accept.restype = ctypes.c_int
+        f64p = ctypes.POINTER(ctypes.c_double)
+        lib.oracle_tree_accept_sample.argtypes = [
+            f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double, i32p, i32p, ctypes.c_int32, f64p, ctypes.c_double,
+            i32p, i32p, i32p, f64p]
+        lib.oracle_tree_accept_sample.restype = ctypes.c_int
         lib.oracle_kv_commit.argtypes = [
             ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
             i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int32,
@@ -210,3 +215,34 @@ def kv_commit_seq(cache, S, path, accepted_len, *, block_table=None, block_size=
                                   _p(path, ctypes.c_int32), int(accepted_len), paged, sh, st,
                                   _p(bt, ctypes.c_int32), block_size, sb, _p(newp, ctypes.c_int32))
     return int(rc), int(newp[0])
+
+
+def tree_accept_sample_seq(logits, draft, parent, temperature, u_accept, u_bonus):
+    """One sequence: logits f32 [T, V]; u_accept [T] and u_bonus in [0, 1).
+    Returns (rc, accepted_len, path int32[T], bonus, margin)."""
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    T, V = lg.shape
+    draft, parent = _i32(draft), _i32(parent)
+    ua = np.ascontiguousarray(u_accept, dtype=np.float64)
+    alen, bonus, margin = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_double(0)
+    path = np.full(T, -1, dtype=np.int32)
+    rc = _load().oracle_tree_accept_sample(_p(lg, ctypes.c_float), V, V, float(temperature), _p(draft, ctypes.c_int32),
+                                           _p(parent, ctypes.c_int32), T, _p(ua, ctypes.c_double), float(u_bonus),
+                                           ctypes.byref(alen), _p(path, ctypes.c_int32), ctypes.byref(bonus),
+                                           ctypes.byref(margin))
+    return int(rc), int(alen.value), path, int(bonus.value), float(margin.value)
+
+
+def tree_accept_sample(logits, draft, parent, temperature, u_accept, u_bonus):
+    """Batch: logits [B,T,V], u_accept [B,T], u_bonus [B] -> (accepted_len [B], path [B,T], bonus [B], margin [B])."""
+    B, T, _ = np.asarray(logits).shape
+    alen = np.zeros(B, dtype=np.int32)
+    path = np.full((B, T), -1, dtype=np.int32)
+    bonus = np.zeros(B, dtype=np.int32)
+    margin = np.zeros(B)
+    for b in range(B):
+        rc, alen[b], path[b], bonus[b], margin[b] = tree_accept_sample_seq(logits[b], draft[b], parent[b], temperature,
+                                                                           u_accept[b], u_bonus[b])
+        if rc != OK:
+            raise ValueError(f"oracle_tree_accept_sample failed with code {rc}")
+    return alen, path, bonus, margin

@@ -48,3 +48,39 @@ def reachability_mask(parent):
                     if reach[k][j]:
                         reach[i][j] = True
     return [sum(1 << j for j in range(T) if reach[i][j]) for i in range(T)]
+
+
+def sample_output_distribution(p_rows, draft, parent, max_tokens=None):
+    """Exact distribution of the token sequence that stochastic tree acceptance emits, by
+    enumerating every outcome of its accept / reject decisions with rational-free float64
+    probabilities. p_rows[i] is the target distribution at node i (a list summing to 1).
+    Returns {tuple of emitted tokens (accepted draft tokens, then the bonus): probability}.
+
+    Written from the rule itself (try the children in node order, accept child c with the
+    residual probability of its token, otherwise delete that token and renormalise; when no
+    child is accepted draw the bonus from what is left) and independent of oracle.c; the
+    tests compare this distribution with the product of target conditionals."""
+    T = len(parent)
+    kids = {i: [c for c in range(i + 1, T) if int(parent[c]) == i] for i in range(T)}
+    out = {}
+
+    def visit(node, prefix, prob):
+        resid = list(p_rows[node])
+        mass = prob                                   # probability of standing here with this residual
+        for c in kids[node]:
+            x = int(draft[c])
+            tot = sum(resid)
+            r = resid[x] / tot if tot > 0 and 0 <= x < len(resid) else 0.0
+            if r > 0:
+                visit(c, prefix + (x,), mass * r)
+                mass *= (1.0 - r)
+                resid[x] = 0.0
+        tot = sum(resid)
+        if mass > 0 and tot > 0:
+            for y, w in enumerate(resid):
+                if w > 0:
+                    key = prefix + (y,)
+                    out[key] = out.get(key, 0.0) + mass * w / tot
+
+    visit(0, (), 1.0)
+    return out

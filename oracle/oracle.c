@@ -26,6 +26,11 @@
  *   oracle_tree_accept  brute-force enumeration of root-to-leaf paths (a
  *       separate implementation in another language), forced full/zero
  *       acceptance, structural invariants of the returned path.
+ *   oracle_tree_accept_sample  exact output distribution by enumeration of the
+ *       decision tree (a separate implementation) equals the target softmax at
+ *       every emitted position, Monte-Carlo chi-square of the same, temperature
+ *       -> 0 equals the greedy rule, u = 0 / u -> 1 extremes, duplicate sibling
+ *       tokens, inverse-CDF sampling against numpy's searchsorted.
  *   oracle_kv_commit  an out-of-place gather from a pristine copy of the cache
  *       (numpy fancy indexing), identity on a chain path, untouched bytes
  *       outside the destination rows, and the closed loop: attention over the
@@ -235,5 +240,94 @@ int oracle_kv_commit(unsigned char* cache, int32_t elem_bytes, int32_t Hkv, int3
             if (src != dst) memmove(cache + dst * elem_bytes, cache + src * elem_bytes, row_bytes);
         }
     *new_prefix = S + accepted_len + 1;
+    return ORACLE_OK;
+}
+
+/* Stochastic acceptance over a draft tree (Section 3.1: a draft token is accepted with
+ * probability min(1, p/p_hat); after a rejection the target distribution is replaced by
+ * norm(max(0, p - p_hat)) and, when no candidate is left, the next token is drawn from it).
+ * Reading for a tree whose candidates come from a deterministic top-k expansion
+ * (Appendix A): the proposal for a candidate is a point mass on its token, p_hat = 1 there
+ * and 0 elsewhere. So, standing at node `cur` with target distribution
+ * p = softmax(logits[cur] / temperature):
+ *   - the children of cur are tried in ascending node order; child c with token x is
+ *     accepted iff u_accept[c] < r(x), r = the current residual distribution;
+ *   - a rejected token is removed: r(x) = 0 and r is renormalised (that is
+ *     norm(max(0, r - p_hat)) for a point mass); a sibling that repeats a removed token, or
+ *     names a token outside the vocabulary, has probability 0;
+ *   - an accepted child becomes cur (with a fresh p from its own logits row);
+ *   - when no child is accepted (or cur is a leaf) the bonus token is drawn from r by
+ *     inverting its cumulative sum in index order with u_bonus:
+ *     bonus = min{ j : sum_{i<=j} r_i > u_bonus * sum_i r_i }.
+ * Every step is an exact rejection scheme, so the emitted tokens are distributed as the
+ * target's own sampling would be.
+ *
+ * u_accept[T] and u_bonus are uniforms in [0,1) supplied by the caller. *margin receives
+ * the smallest distance between a uniform and the threshold it was compared with
+ * (accept tests: |u - r(x)|; bonus: distance of u_bonus to the two cumulative sums that
+ * bracket it, relative to the total), so that a caller comparing against an fp32
+ * implementation can tell a knife-edge decision from a wrong one. */
+int oracle_tree_accept_sample(const float* logits, int64_t ld, int32_t V, double temperature,
+                              const int32_t* draft, const int32_t* parent, int32_t T,
+                              const double* u_accept, double u_bonus, int32_t* accepted_len,
+                              int32_t* path, int32_t* bonus, double* margin) {
+    int rc = oracle_tree_validate(parent, T);
+    if (rc != ORACLE_OK) return rc;
+    if (V < 1 || !(temperature > 0.0)) return ORACLE_BAD_SIZE;
+    double* e = (double*)malloc((size_t)V * sizeof(double));
+    if (!e) return ORACLE_BAD_SIZE;
+    for (int32_t k = 0; k < T; ++k) path[k] = -1;
+    double mg = 1.0;
+    int32_t cur = 0, len = 0;
+    path[0] = 0;
+    for (;;) {
+        const float* row = logits + (int64_t)cur * ld;
+        double m = -INFINITY;
+        for (int32_t j = 0; j < V; ++j) {
+            double z = (double)row[j] / temperature;
+            if (z > m) m = z;
+        }
+        for (int32_t j = 0; j < V; ++j) e[j] = exp((double)row[j] / temperature - m);
+        int32_t next = -1;
+        for (int32_t c = cur + 1; c < T && next < 0; ++c) {
+            if (parent[c] != cur) continue;
+            double total = 0.0; /* residual mass, summed afresh */
+            for (int32_t j = 0; j < V; ++j) total += e[j];
+            const int32_t x = draft[c];
+            const double r = (x >= 0 && x < V && total > 0.0) ? e[x] / total : 0.0;
+            const double dist = fabs(u_accept[c] - r);
+            if (dist < mg) mg = dist;
+            if (u_accept[c] < r) next = c;
+            else if (x >= 0 && x < V) e[x] = 0.0;
+        }
+        if (next >= 0) {
+            cur = next;
+            path[++len] = cur;
+            continue;
+        }
+        double total = 0.0;
+        for (int32_t j = 0; j < V; ++j) total += e[j];
+        const double target = u_bonus * total;
+        double acc = 0.0;
+        int32_t pick = -1, last_pos = -1;
+        for (int32_t j = 0; j < V; ++j) {
+            if (e[j] > 0.0) last_pos = j;
+            const double before = acc;
+            acc += e[j];
+            if (acc > target) {
+                pick = j;
+                const double d0 = (target - before) / total, d1 = (acc - target) / total;
+                if (before > 0.0 && d0 < mg) mg = d0;
+                if (d1 < mg) mg = d1;
+                break;
+            }
+        }
+        if (pick < 0) pick = last_pos; /* u_bonus * total rounded up to the whole mass */
+        *bonus = pick;
+        break;
+    }
+    *accepted_len = len;
+    *margin = mg;
+    free(e);
     return ORACLE_OK;
 }
