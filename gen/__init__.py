@@ -27,6 +27,8 @@ STREAM_PLANT = 7
 STREAM_PREFIX = 8
 STREAM_BLOCKS = 9
 STREAM_PATH = 10
+STREAM_UNIFORM = 11
+STREAM_CANDIDATE = 12
 
 
 def rng(seed: int, stream: int, sub: int = 0) -> np.random.Generator:
@@ -376,3 +378,26 @@ def random_accept_path(g: np.random.Generator, parent: np.ndarray, full: bool = 
         path[depth[j]] = j
         j = int(parent[j])
     return path, int(depth[end])
+
+
+def uniforms(seed: int, B: int, T: int):
+    """The random numbers a stochastic acceptance consumes, as inputs: u_accept f32 [B,T] and
+    u_bonus f32 [B], uniform in [0, 1) (24 random bits each, so the fp32 value is exact)."""
+    g = rng(seed, STREAM_UNIFORM)
+    ua = (g.integers(0, 1 << 24, size=(B, T)).astype(np.float32) / np.float32(1 << 24)).astype(np.float32)
+    ub = (g.integers(0, 1 << 24, size=(B,)).astype(np.float32) / np.float32(1 << 24)).astype(np.float32)
+    return ua, ub
+
+
+def logits_with_candidates(g_logits: np.random.Generator, g_cand: np.random.Generator, parent: np.ndarray,
+                           tokens: np.ndarray, V: int, spread: float = 1.5) -> np.ndarray:
+    """Logits for stochastic acceptance: N(0,1) rows in which every child's token is raised to
+    about the level where one candidate holds a sizeable share of its parent's softmax mass
+    (log of the row's expected background mass V*sqrt(e), plus N(0, spread^2)), the way a draft
+    model's top-k candidates sit among the target's likely tokens. f32 [T, V]."""
+    T = len(parent)
+    lg = g_logits.standard_normal((T, V), dtype=np.float32)
+    level = np.log(V) + 0.5
+    for c in range(1, T):
+        lg[parent[c], tokens[c]] = np.float32(level + spread * g_cand.standard_normal())
+    return lg

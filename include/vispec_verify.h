@@ -12,6 +12,8 @@
  *                             of the T tree queries over prefix + visible tree keys
  *   vs_tree_accept            vocab-wide argmax per node, longest accepted path and
  *                             bonus token (Section 3.1 at temperature 0)
+ *   vs_tree_accept_sample     the same walk at a temperature > 0: accept with probability
+ *                             min(1, p/p_hat), residual resampling (Section 3.1)
  *   vs_tree_kv_commit         keeps the accepted path's K/V rows, in order, behind the
  *                             prefix of the pre-allocated cache (Section 3.1, Appendix A)
  *
@@ -203,6 +205,44 @@ int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V,
                        int32_t* accepted_len, int32_t* path, int32_t* bonus_token,
                        int32_t* row_argmax, int32_t* status, void* workspace,
                        size_t workspace_bytes, void* stream);
+
+size_t vs_accept_sample_workspace_bytes(int32_t B, int32_t T, int32_t V); /* 0 for unsupported sizes */
+
+/*
+ * Stochastic acceptance (Section 3.1: a draft token is accepted with probability
+ * min(1, p/p_hat); after a rejection the target distribution becomes norm(max(0, p - p_hat)),
+ * and when no candidate is left the next token is drawn from it). The candidates of a tree
+ * built by deterministic top-k expansion (Appendix A) are point-mass proposals, so, standing
+ * at a node with residual distribution r (initially softmax(logits / temperature) of that
+ * node's row): its children are tried in ascending node order; child c with token x is
+ * accepted iff u_accept[c] < r(x) and becomes the current node; a rejected token is removed
+ * from r, which is renormalised (a sibling repeating a removed token, or naming a token
+ * outside [0, V), has probability 0); when no child is accepted the bonus token is
+ * min{ j : sum_{i<=j} r_i > u_bonus * sum_i r_i }. The emitted tokens are distributed exactly
+ * as sampling from the target would distribute them. The random numbers are inputs, so the
+ * call is a deterministic function of its arguments.
+ *   logits       [B,T,ld_logits] fp32 in; every row needs at least one finite entry, -inf
+ *                entries have probability 0, no NaN; ld_logits >= V; V <= 8388608
+ *   temperature  > 0, finite
+ *   draft_tokens [B,T] int32 in; entry 0 is ignored
+ *   parent       [B,T] int32 in
+ *   u_accept     [B,T] fp32 in, uniform in [0,1); entry 0 is ignored
+ *   u_bonus      [B] fp32 in, uniform in [0,1)
+ *   accepted_len [B] int32 out; number of accepted draft tokens
+ *   path         [B,T] int32 out; path[b][0..accepted_len[b]] = root .. last accepted node, rest -1
+ *   bonus_token  [B] int32 out
+ *   status       [B] int32 out, optional
+ *   workspace    at least vs_accept_sample_workspace_bytes(B,T,V) bytes, 256-byte aligned
+ * Arithmetic is fp32 (exp2 of the hardware, sums over 4096-entry chunks merged per row), so a
+ * uniform that lies within ~1e-5 of its threshold may fall on the other side than in exact
+ * arithmetic; either outcome is a valid draw.
+ */
+int32_t vs_tree_accept_sample(const float* logits, int64_t ld_logits, int32_t V, float temperature,
+                              const int32_t* draft_tokens, const int32_t* parent,
+                              const float* u_accept, const float* u_bonus, int32_t B, int32_t T,
+                              int32_t* accepted_len, int32_t* path, int32_t* bonus_token,
+                              int32_t* status, void* workspace, size_t workspace_bytes,
+                              void* stream);
 
 /*
  * KV caches of one or more layers that share a layout (host struct, read during the call).

@@ -58,6 +58,10 @@ def _load():
             f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double, i32p, i32p, ctypes.c_int32, f64p, ctypes.c_double,
             i32p, i32p, i32p, f64p]
         lib.oracle_tree_accept_sample.restype = ctypes.c_int
+        lib.oracle_tree_accept_sample_check.argtypes = [
+            f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double, i32p, i32p, ctypes.c_int32, f64p, ctypes.c_double,
+            ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_double, f64p]
+        lib.oracle_tree_accept_sample_check.restype = ctypes.c_int
         lib.oracle_kv_commit.argtypes = [
             ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
             i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int32,
@@ -231,6 +235,22 @@ def tree_accept_sample_seq(logits, draft, parent, temperature, u_accept, u_bonus
                                            ctypes.byref(alen), _p(path, ctypes.c_int32), ctypes.byref(bonus),
                                            ctypes.byref(margin))
     return int(rc), int(alen.value), path, int(bonus.value), float(margin.value)
+
+
+def tree_accept_sample_check_seq(logits, draft, parent, temperature, u_accept, u_bonus, accepted_len, path, bonus,
+                                 eps):
+    """Is the claimed outcome one the rule can produce when each uniform-vs-threshold comparison
+    may be off by eps? Returns (rc, worst): rc 0 = yes; worst = largest wrong-side distance."""
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    T, V = lg.shape
+    draft, parent, path = _i32(draft), _i32(parent), _i32(path)
+    ua = np.ascontiguousarray(u_accept, dtype=np.float64)
+    worst = ctypes.c_double(0)
+    rc = _load().oracle_tree_accept_sample_check(_p(lg, ctypes.c_float), V, V, float(temperature),
+                                                 _p(draft, ctypes.c_int32), _p(parent, ctypes.c_int32), T,
+                                                 _p(ua, ctypes.c_double), float(u_bonus), int(accepted_len),
+                                                 _p(path, ctypes.c_int32), int(bonus), float(eps), ctypes.byref(worst))
+    return int(rc), float(worst.value)
 
 
 def tree_accept_sample(logits, draft, parent, temperature, u_accept, u_bonus):

@@ -331,3 +331,80 @@ int oracle_tree_accept_sample(const float* logits, int64_t ld, int32_t V, double
     free(e);
     return ORACLE_OK;
 }
+
+/* Is (accepted_len, path, bonus) an outcome of the stochastic acceptance above when every
+ * comparison of a uniform with its threshold is allowed to be off by `eps` (absolute, in
+ * probability)? The walk is replayed along the claimed path with the same rule, same order,
+ * same fp64 arithmetic as oracle_tree_accept_sample:
+ *   - a child tried before the claimed next node must have been rejected: u >= r(x) - eps;
+ *   - the claimed next node must be a child of the current one, accepted: u < r(x) + eps;
+ *   - after the last node of the path every child must have been rejected, and the bonus
+ *     token must carry weight and bracket the target: with C the cumulative sum of the
+ *     residual r in index order, C(bonus-1) - eps <= u_bonus and u_bonus < C(bonus) + eps.
+ * With eps = 0 exactly one outcome passes: the one oracle_tree_accept_sample returns (except
+ * that a u_bonus so close to 1 that u_bonus * total rounds up to the whole mass makes that
+ * routine fall back to the last weighted token; here any eps > 0 admits it). An fp32
+ * implementation whose probabilities are within eps of the exact ones must pass with that eps.
+ * *worst receives the largest amount by which a comparison was on the wrong side (<= 0 when
+ * every exact comparison agrees). Returns ORACLE_OK or ORACLE_BAD_PATH. */
+int oracle_tree_accept_sample_check(const float* logits, int64_t ld, int32_t V, double temperature,
+                                    const int32_t* draft, const int32_t* parent, int32_t T,
+                                    const double* u_accept, double u_bonus, int32_t accepted_len,
+                                    const int32_t* path, int32_t bonus, double eps, double* worst) {
+    int rc = oracle_tree_validate(parent, T);
+    if (rc != ORACLE_OK) return rc;
+    if (V < 1 || !(temperature > 0.0)) return ORACLE_BAD_SIZE;
+    if (accepted_len < 0 || accepted_len >= T || path[0] != 0) return ORACLE_BAD_PATH;
+    double* e = (double*)malloc((size_t)V * sizeof(double));
+    if (!e) return ORACLE_BAD_SIZE;
+    double w = -1.0;
+    int ok = 1;
+    for (int32_t k = 0; k <= accepted_len && ok; ++k) {
+        const int32_t cur = path[k];
+        const int32_t want = (k < accepted_len) ? path[k + 1] : -1;
+        if (cur < 0 || cur >= T) { ok = 0; break; }
+        if (want >= 0 && (want <= cur || want >= T || parent[want] != cur)) { ok = 0; break; }
+        const float* row = logits + (int64_t)cur * ld;
+        double m = -INFINITY;
+        for (int32_t j = 0; j < V; ++j) {
+            double z = (double)row[j] / temperature;
+            if (z > m) m = z;
+        }
+        for (int32_t j = 0; j < V; ++j) e[j] = exp((double)row[j] / temperature - m);
+        for (int32_t c = cur + 1; c < T; ++c) {
+            if (parent[c] != cur) continue;
+            double total = 0.0;
+            for (int32_t j = 0; j < V; ++j) total += e[j];
+            const int32_t x = draft[c];
+            const double r = (x >= 0 && x < V && total > 0.0) ? e[x] / total : 0.0;
+            if (c == want) {
+                const double off = u_accept[c] - r; /* accepted needs u < r */
+                if (off > w) w = off;
+                if (!(u_accept[c] < r + eps)) ok = 0;
+                break;
+            }
+            const double off = r - u_accept[c]; /* rejected needs u >= r */
+            if (off > w) w = off;
+            if (!(u_accept[c] >= r - eps)) ok = 0;
+            if (x >= 0 && x < V) e[x] = 0.0;
+        }
+        if (want < 0 && ok) {
+            double total = 0.0;
+            for (int32_t j = 0; j < V; ++j) total += e[j];
+            if (bonus < 0 || bonus >= V || !(e[bonus] > 0.0) || !(total > 0.0)) { ok = 0; break; }
+            double before = 0.0;
+            for (int32_t j = 0; j < bonus; ++j) before += e[j];
+            const double lo = before / total, hi = (before + e[bonus]) / total;
+            const double off_lo = lo - u_bonus;  /* needs C(bonus-1) <= u */
+            const double off_hi = u_bonus - hi;  /* needs u < C(bonus)  */
+            if (off_lo > w) w = off_lo;
+            if (off_hi > w) w = off_hi;
+            if (!(u_bonus >= lo - eps) || !(u_bonus < hi + eps)) ok = 0;
+        }
+    }
+    for (int32_t k = accepted_len + 1; k < T && ok; ++k)
+        if (path[k] != -1) ok = 0;
+    *worst = w;
+    free(e);
+    return ok ? ORACLE_OK : ORACLE_BAD_PATH;
+}

@@ -14,7 +14,8 @@ VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED = 0, 1, 2
 EXPORTED_SYMBOLS = [
     "vs_version", "vs_strerror", "vs_status_string", "vs_tree_validate_host", "vs_tree_mask_build",
     "vs_attention_plan", "vs_attention_workspace_bytes", "vs_tree_verify_attention",
-    "vs_accept_workspace_bytes", "vs_tree_accept", "vs_tree_kv_commit",
+    "vs_accept_workspace_bytes", "vs_tree_accept", "vs_accept_sample_workspace_bytes", "vs_tree_accept_sample",
+    "vs_tree_kv_commit",
 ]
 
 
@@ -93,6 +94,11 @@ def lib():
         L.vs_accept_workspace_bytes.restype = sz
         L.vs_tree_accept.argtypes = [vp, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vs_tree_accept.restype = i32
+        L.vs_accept_sample_workspace_bytes.argtypes = [i32, i32, i32]
+        L.vs_accept_sample_workspace_bytes.restype = sz
+        L.vs_tree_accept_sample.argtypes = [vp, i64, i32, ctypes.c_float, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp,
+                                            sz, vp]
+        L.vs_tree_accept_sample.restype = i32
         L.vs_tree_kv_commit.argtypes = [ctypes.POINTER(KVDesc), vp, vp, vp, vp, vp, vp, vp, vp]
         L.vs_tree_kv_commit.restype = i32
         _lib = L
@@ -159,6 +165,19 @@ def vs_tree_accept(logits, ld_logits, V, draft_tokens, parent, B, T, accepted_le
     return lib().vs_tree_accept(_ptr(logits), ld_logits, V, _ptr(draft_tokens), _ptr(parent), B, T,
                                 _ptr(accepted_len), _ptr(path), _ptr(bonus_token), _ptr(row_argmax),
                                 _ptr(status), _ptr(workspace), workspace_bytes, _ptr(stream))
+
+
+def vs_accept_sample_workspace_bytes(B: int, T: int, V: int) -> int:
+    return lib().vs_accept_sample_workspace_bytes(B, T, V)
+
+
+def vs_tree_accept_sample(logits, ld_logits, V, temperature, draft_tokens, parent, u_accept, u_bonus, B, T,
+                          accepted_len, path, bonus_token, status=None, workspace=None, workspace_bytes=0,
+                          stream=None) -> int:
+    return lib().vs_tree_accept_sample(_ptr(logits), ld_logits, V, temperature, _ptr(draft_tokens), _ptr(parent),
+                                       _ptr(u_accept), _ptr(u_bonus), B, T, _ptr(accepted_len), _ptr(path),
+                                       _ptr(bonus_token), _ptr(status), _ptr(workspace), workspace_bytes,
+                                       _ptr(stream))
 
 
 def vs_tree_kv_commit(desc: KVDesc, k_cache, v_cache, prefix_len, path, accepted_len, new_prefix_len,

@@ -348,6 +348,48 @@ int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V, const 
     return launch_accept(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
 }
 
+size_t vs_accept_sample_workspace_bytes(int32_t B, int32_t T, int32_t V) {
+    if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1 || accept_chunks(V) > kMaxSampleChunks) return 0;
+    const size_t n = (size_t)B * T * accept_chunks(V);
+    return 2 * align_up(n * sizeof(float));
+}
+
+int32_t vs_tree_accept_sample(const float* logits, int64_t ld_logits, int32_t V, float temperature,
+                              const int32_t* draft_tokens, const int32_t* parent, const float* u_accept,
+                              const float* u_bonus, int32_t B, int32_t T, int32_t* accepted_len, int32_t* path,
+                              int32_t* bonus_token, int32_t* status, void* workspace, size_t workspace_bytes_given,
+                              void* stream) {
+    if (!logits || !draft_tokens || !parent || !u_accept || !u_bonus || !accepted_len || !path || !bonus_token)
+        return VS_ERR_NULL;
+    if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1 || ld_logits < V) return VS_ERR_SHAPE;
+    if (accept_chunks(V) > kMaxSampleChunks) return VS_ERR_SHAPE;
+    if (!(temperature > 0.f) || !(temperature < INFINITY)) return VS_ERR_SHAPE;
+    const size_t need = vs_accept_sample_workspace_bytes(B, T, V);
+    if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;
+    SampleParams p{};
+    p.logits = logits;
+    p.ld = ld_logits;
+    p.V = V;
+    p.draft = draft_tokens;
+    p.parent = parent;
+    p.u_accept = u_accept;
+    p.u_bonus = u_bonus;
+    p.B = B;
+    p.T = T;
+    p.accepted_len = accepted_len;
+    p.path = path;
+    p.bonus = bonus_token;
+    p.status = status;
+    p.k_log2 = 1.4426950408889634f / temperature;
+    p.chunks = accept_chunks(V);
+    p.chunk_elems = kArgmaxChunk;
+    p.vec_ok = (aligned16(logits) && ld_logits % 4 == 0) ? 1 : 0;
+    const size_t n = (size_t)B * T * p.chunks;
+    p.part_m = (float*)workspace;
+    p.part_s = (float*)((char*)workspace + align_up(n * sizeof(float)));
+    return launch_accept_sample(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
+}
+
 int32_t vs_tree_kv_commit(const vs_kv_desc* d, void* k_cache, void* v_cache, const int32_t* prefix_len,
                           const int32_t* path, const int32_t* accepted_len, int32_t* new_prefix_len,
                           int32_t* status, void* stream) {

@@ -63,6 +63,29 @@ struct AcceptParams {
     int32_t vec_ok;      // rows are 16-byte aligned → float4 loads
 };
 
+constexpr int kMaxSampleChunks = 2048; // chunk sums of one logits row kept in LDS by the sampling walk
+
+struct SampleParams {
+    const float* logits;
+    int64_t ld;
+    int32_t V;
+    const int32_t* draft;
+    const int32_t* parent;
+    const float* u_accept; // [B][T]
+    const float* u_bonus;  // [B]
+    int32_t B, T;
+    int32_t* accepted_len;
+    int32_t* path;
+    int32_t* bonus;
+    int32_t* status;       // may be null
+    float* part_m;         // [B*T][chunks] chunk maximum of the raw logits
+    float* part_s;         // [B*T][chunks] sum of 2^((l - chunk maximum) * k_log2)
+    float k_log2;          // log2(e) / temperature
+    int32_t chunks;
+    int32_t chunk_elems;   // 4096
+    int32_t vec_ok;        // rows are 16-byte aligned → float4 loads
+};
+
 struct CommitParams {
     void* k;
     void* v;
@@ -97,6 +120,7 @@ bool attention_pipe_supported(int rpw, int waves);
 hipError_t launch_attention_mfma_pipe(const AttnParams& p, int rpw, int waves, hipStream_t s);
 hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
+hipError_t launch_accept_sample(const SampleParams& p, hipStream_t s);
 hipError_t launch_kv_commit(const CommitParams& p, hipStream_t s);
 
 } // namespace vs

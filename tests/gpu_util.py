@@ -129,6 +129,31 @@ def run_accept(logits: np.ndarray, tokens: np.ndarray, parent: np.ndarray, ld=No
     return (amax.cpu().numpy(), alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy(), status.cpu().numpy())
 
 
+def run_accept_sample(logits: np.ndarray, tokens: np.ndarray, parent: np.ndarray, temperature: float,
+                      u_accept: np.ndarray, u_bonus: np.ndarray, ld=None, offset_elems=0):
+    """logits [B,T,V]; uniforms f32 [B,T] and [B]; optional row stride and start offset as in run_accept."""
+    B, T, V = logits.shape
+    ld = V if ld is None else ld
+    buf = torch.full((B * T * ld + offset_elems + 8,), float("nan"), device="cuda", dtype=torch.float32)
+    view = buf[offset_elems:offset_elems + B * T * ld].view(B * T, ld)
+    view[:, :V] = dev(logits.reshape(B * T, V))
+    tok = dev(tokens.astype(np.int32))
+    par = dev(parent.astype(np.int32))
+    ua = dev(np.asarray(u_accept, dtype=np.float32))
+    ub = dev(np.asarray(u_bonus, dtype=np.float32))
+    alen = torch.full((B,), -7, device="cuda", dtype=torch.int32)
+    path = torch.full((B, T), -7, device="cuda", dtype=torch.int32)
+    bonus = torch.full((B,), -7, device="cuda", dtype=torch.int32)
+    status = torch.full((B,), -99, device="cuda", dtype=torch.int32)
+    nbytes = vs.vs_accept_sample_workspace_bytes(B, T, V)
+    ws = torch.empty(nbytes, device="cuda", dtype=torch.uint8)
+    rc = vs.vs_tree_accept_sample(view.data_ptr(), ld, V, float(temperature), tok, par, ua, ub, B, T, alen, path,
+                                  bonus, status, ws, nbytes, stream_ptr())
+    assert rc == 0, vs.vs_strerror(rc)
+    torch.cuda.synchronize()
+    return alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy(), status.cpu().numpy()
+
+
 class DeviceCommit:
     """Device copies of L layers of K/V caches (stacked along a leading layer axis) plus the
     descriptor of vs_tree_kv_commit. `k_layers` / `v_layers`: numpy [L, ...one layer's cache...]

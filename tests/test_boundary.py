@@ -148,6 +148,29 @@ def test_calls_reject_bad_arguments_before_any_launch():
     assert vs.vs_tree_accept(good, 10, 10, good, good, 1, 4, good, good, good, None, None, good, 8) == -4
 
 
+def test_accept_sample_rejects_bad_arguments_before_any_launch():
+    g = 4096  # never dereferenced
+    n = vs.vs_accept_sample_workspace_bytes(1, 60, 152064)
+    assert n >= 2 * 60 * 38 * 4
+    assert vs.vs_accept_sample_workspace_bytes(1, 65, 10) == 0
+    assert vs.vs_accept_sample_workspace_bytes(1, 4, 8388608) > 0
+    assert vs.vs_accept_sample_workspace_bytes(1, 4, 8388609) == 0            # more chunks than the walk keeps
+    ok = dict(workspace=g, workspace_bytes=1 << 20)
+    assert vs.vs_tree_accept_sample(None, 10, 10, 1.0, g, g, g, g, 1, 4, g, g, g, **ok) == -1
+    assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, None, g, 1, 4, g, g, g, **ok) == -1   # uniforms are required
+    assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, g, None, 1, 4, g, g, g, **ok) == -1
+    assert vs.vs_tree_accept_sample(g, 9, 10, 1.0, g, g, g, g, 1, 4, g, g, g, **ok) == -2
+    assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, g, g, 1, 65, g, g, g, **ok) == -2
+    assert vs.vs_tree_accept_sample(g, 10, 10, 0.0, g, g, g, g, 1, 4, g, g, g, **ok) == -2       # temperature 0: greedy call
+    assert vs.vs_tree_accept_sample(g, 10, 10, -1.0, g, g, g, g, 1, 4, g, g, g, **ok) == -2
+    assert vs.vs_tree_accept_sample(g, 10, 10, float("nan"), g, g, g, g, 1, 4, g, g, g, **ok) == -2
+    assert vs.vs_tree_accept_sample(g, 10, 10, float("inf"), g, g, g, g, 1, 4, g, g, g, **ok) == -2
+    assert vs.vs_tree_accept_sample(g, 1 << 24, 8388609, 1.0, g, g, g, g, 1, 4, g, g, g, **ok) == -2
+    assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, g, g, 1, 4, g, g, g) == -4
+    assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, g, g, 1, 4, g, g, g, None, g, 8) == -4
+    assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, g, g, 1, 4, g, g, g, None, g + 8, 1 << 20) == -4
+
+
 def test_kv_commit_rejects_bad_arguments_before_any_launch():
     def kd(**kw):
         d = vs.KVDesc(B=2, T=8, Hkv=2, d=64, dtype=vs.VS_BF16, num_layers=3, stride_layer=2 * 2 * 100 * 64,

@@ -153,3 +153,57 @@ def test_malformed_inputs(oracle_mod):
     # a draft token outside the vocabulary has probability 0
     rc, alen, path, bonus, _ = oracle_mod.tree_accept_sample_seq(logits, [0, 9, -4], [-1, 0, 0], 1.0, np.zeros(3), 0.5)
     assert rc == 0 and alen == 0
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_outcome_check_admits_exactly_the_rule_s_outcome(oracle_mod, seed):
+    """oracle_tree_accept_sample_check with eps = 0: the walk's own result passes, every
+    neighbouring claim (another bonus token, a shorter or longer path, a sibling) fails."""
+    T, V = 9, 40
+    parent, draft, logits = _small_case(50 + seed, T, V)
+    g = gen.rng(seed, gen.STREAM_PATH)
+    ua, ub = g.random(T), float(g.random())
+    rc, alen, path, bonus, margin = oracle_mod.tree_accept_sample_seq(logits, draft, parent, 1.0, ua, ub)
+    chk = lambda a, p, bo, eps=0.0: oracle_mod.tree_accept_sample_check_seq(logits, draft, parent, 1.0, ua, ub, a, p,
+                                                                           bo, eps)
+    rc, worst = chk(alen, path, bonus)
+    assert rc == 0 and worst <= 0.0 and abs(-worst - margin) < 1e-12   # the closest call is the margin
+    for other in range(V):
+        if other != bonus:
+            assert chk(alen, path, other)[0] != 0
+    if alen > 0:                                                # stopping early: the accepted child was "rejected"
+        short = path.copy(); short[alen] = -1
+        for bo in range(V):
+            assert chk(alen - 1, short, bo)[0] != 0
+    kids = [c for c in range(T) if parent[c] == path[alen]]
+    for c in kids:                                              # going further: a rejected child was "accepted"
+        longer = path.copy(); longer[alen + 1] = c
+        assert all(chk(alen + 1, longer, bo)[0] != 0 for bo in range(V))
+    bad = path.copy(); bad[0] = 1
+    assert chk(alen, bad, bonus)[0] != 0
+    stray = path.copy(); stray[T - 1] = 3 if alen < T - 1 else stray[T - 1]
+    if alen < T - 1:
+        assert chk(alen, stray, bonus)[0] != 0                  # entries past the path must be -1
+
+
+def test_outcome_check_tolerance_admits_only_knife_edges(oracle_mod):
+    """Root row weights 4:2:1:1 (probabilities .5 .25 .125 .125), child token 1 (p = .25)."""
+    logits = np.log(np.array([[4, 2, 1, 1], [1, 1, 1, 1]], dtype=np.float64)).astype(np.float32)
+    draft, parent = [0, 1], [-1, 0]
+    acc, rej = np.array([0, 1, -1], dtype=np.int32)[:2], np.array([0, -1], dtype=np.int32)
+    chk = lambda ua1, ub, a, p, bo, eps: oracle_mod.tree_accept_sample_check_seq(
+        logits, draft, parent, 1.0, [0.0, ua1], ub, a, p, bo, eps)[0]
+    # u = .25 + 1e-7 rejects exactly; "accepted" is admitted with eps = 1e-6 but not with 1e-8
+    assert chk(0.25 + 1e-7, 0.1, 0, rej, 0, 0.0) == 0
+    assert chk(0.25 + 1e-7, 0.1, 1, acc, 0, 0.0) != 0
+    assert chk(0.25 + 1e-7, 0.1, 1, acc, 0, 1e-6) == 0
+    assert chk(0.25 + 1e-7, 0.1, 1, acc, 0, 1e-8) != 0
+    # a clear rejection is never admitted as accepted, whatever small eps
+    assert chk(0.6, 0.1, 1, acc, 0, 1e-3) != 0
+    # bonus after the rejection: residual 4:0:1:1 -> cumulative 2/3, 2/3, 5/6, 1; token 1 has no weight
+    assert chk(0.6, 0.5, 0, rej, 0, 0.0) == 0
+    assert chk(0.6, 0.7, 0, rej, 2, 0.0) == 0
+    assert chk(0.6, 0.7, 0, rej, 1, 1.0) != 0                   # removed token: never, whatever eps
+    assert chk(0.6, 2 / 3 + 1e-7, 0, rej, 0, 0.0) != 0
+    assert chk(0.6, 2 / 3 + 1e-7, 0, rej, 0, 1e-6) == 0         # within eps of token 0's bracket
+    assert chk(0.6, 2 / 3 + 1e-7, 0, rej, 3, 1e-6) != 0
