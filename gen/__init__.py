@@ -401,3 +401,14 @@ def logits_with_candidates(g_logits: np.random.Generator, g_cand: np.random.Gene
     for c in range(1, T):
         lg[parent[c], tokens[c]] = np.float32(level + spread * g_cand.standard_normal())
     return lg
+
+
+STREAM_DRAFT = 13
+
+
+def draft_logits(seed: int, b: int, level: int, F: int, V: int, sharp: float = 3.0) -> np.ndarray:
+    """Stand-in for a draft model's output at the F frontier nodes of one expansion step:
+    f32 [F, V], N(0, sharp^2) so that a handful of tokens hold most of each row's mass, as a
+    trained draft head's logits do."""
+    g = rng(seed, STREAM_DRAFT, b * 64 + level)
+    return (sharp * g.standard_normal((F, V), dtype=np.float32)).astype(np.float32)

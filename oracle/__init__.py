@@ -62,6 +62,12 @@ def _load():
             f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_double, i32p, i32p, ctypes.c_int32, f64p, ctypes.c_double,
             ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_double, f64p]
         lib.oracle_tree_accept_sample_check.restype = ctypes.c_int
+        lib.oracle_draft_expand.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, f32p, ctypes.c_int32, ctypes.c_int32,
+                                            i32p, f64p, i32p, f64p]
+        lib.oracle_draft_expand.restype = ctypes.c_int
+        lib.oracle_draft_tree_build.argtypes = [i32p, f32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                i32p, i32p, i32p, i32p]
+        lib.oracle_draft_tree_build.restype = ctypes.c_int
         lib.oracle_kv_commit.argtypes = [
             ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
             i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int32,
@@ -266,3 +272,35 @@ def tree_accept_sample(logits, draft, parent, temperature, u_accept, u_bonus):
         if rc != OK:
             raise ValueError(f"oracle_tree_accept_sample failed with code {rc}")
     return alen, path, bonus, margin
+
+
+def draft_expand_seq(logits, cum_in, K):
+    """One expansion step of one sequence: logits f32 [F,V], cum_in f32 [F].
+    Returns (rc, cand_token int32[F*K], cand_score f64[F*K], frontier int32[min(K,F*K)], cut_gap)."""
+    lg = np.ascontiguousarray(logits, dtype=np.float32)
+    F, V = lg.shape
+    cum = np.ascontiguousarray(cum_in, dtype=np.float32)
+    tok = np.full(F * K, -1, dtype=np.int32)
+    sc = np.zeros(F * K, dtype=np.float64)
+    fr = np.full(min(K, F * K), -1, dtype=np.int32)
+    gap = ctypes.c_double(0)
+    rc = _load().oracle_draft_expand(_p(lg, ctypes.c_float), V, V, _p(cum, ctypes.c_float), F, K,
+                                     _p(tok, ctypes.c_int32), _p(sc, ctypes.c_double), _p(fr, ctypes.c_int32),
+                                     ctypes.byref(gap))
+    return int(rc), tok, sc, fr, float(gap.value)
+
+
+def draft_tree_build_seq(cand_token, cand_score, cand_parent, N, root_token=-1):
+    """Final selection of one sequence. Returns (rc, parent int32[T], tokens int32[T], node_cand int32[T])."""
+    tok, par = _i32(cand_token), _i32(cand_parent)
+    sc = np.ascontiguousarray(cand_score, dtype=np.float32)
+    M = len(tok)
+    parent = np.full(N + 1, -1, dtype=np.int32)
+    tokens = np.full(N + 1, -1, dtype=np.int32)
+    node_cand = np.full(N + 1, -1, dtype=np.int32)
+    T = ctypes.c_int32(0)
+    rc = _load().oracle_draft_tree_build(_p(tok, ctypes.c_int32), _p(sc, ctypes.c_float), _p(par, ctypes.c_int32), M, N,
+                                         int(root_token), _p(parent, ctypes.c_int32), _p(tokens, ctypes.c_int32),
+                                         _p(node_cand, ctypes.c_int32), ctypes.byref(T))
+    t = int(T.value) if rc == OK else 0
+    return int(rc), parent[:t], tokens[:t], node_cand[:t]

@@ -84,3 +84,39 @@ def sample_output_distribution(p_rows, draft, parent, max_tokens=None):
 
     visit(0, (), 1.0)
     return out
+
+
+def best_closed_subset(scores, parent, N):
+    """Exhaustive search for the draft tree's final selection (tiny inputs only): among all sets
+    of min(N, M) candidates that contain the parent of each member, the one with the largest
+    total probability sum(exp(score)). Returns the sorted tuple of candidate indices. A route
+    that never sorts by score, to check the oracle's "take the N best scores" against what that
+    rule is claimed to achieve."""
+    import itertools
+    import math
+    M = len(scores)
+    n = min(N, M)
+    best, best_val = None, -1.0
+    for sub in itertools.combinations(range(M), n):
+        s = set(sub)
+        if any(parent[c] >= 0 and parent[c] not in s for c in sub):
+            continue
+        val = sum(math.exp(scores[c]) for c in sub)
+        if val > best_val:
+            best, best_val = sub, val
+    return best
+
+
+def expand_frontier_bruteforce(logits_rows, cum_in, K):
+    """One expansion step by full sorting in Python (independent of oracle.c): returns
+    (tokens, scores, kept candidate indices ascending)."""
+    import math
+    toks, scs = [], []
+    for f, row in enumerate(logits_rows):
+        m = max(row)
+        lse = m + math.log(math.fsum(math.exp(x - m) for x in row))
+        order = sorted(range(len(row)), key=lambda j: (-row[j], j))[:K]
+        toks += order
+        scs += [cum_in[f] + (row[j] - lse) for j in order]
+    keep = sorted(sorted(range(len(scs)), key=lambda c: (-scs[c], c))[:K])
+    return toks, scs, keep

@@ -31,6 +31,13 @@
  *       every emitted position, Monte-Carlo chi-square of the same, temperature
  *       -> 0 equals the greedy rule, u = 0 / u -> 1 extremes, duplicate sibling
  *       tokens, inverse-CDF sampling against numpy's searchsorted.
+ *   oracle_tree_accept_sample_check  admits the walk's own outcome and nothing else at
+ *       eps = 0; hand-worked knife-edge cases for eps > 0.
+ *   oracle_draft_expand  numpy stable argsort and an independent log-softmax for tokens
+ *       and scores, a hand-worked example, brute-force frontier.
+ *   oracle_draft_tree_build  exhaustive search over ancestor-closed subsets on tiny
+ *       candidate sets (the selection maximises total probability), K = 1 gives a chain,
+ *       structural invariants, a hand-worked example.
  *   oracle_kv_commit  an out-of-place gather from a pristine copy of the cache
  *       (numpy fancy indexing), identity on a chain path, untouched bytes
  *       outside the destination rows, and the closed loop: attention over the
@@ -407,4 +414,122 @@ int oracle_tree_accept_sample_check(const float* logits, int64_t ld, int32_t V, 
     *worst = w;
     free(e);
     return ok ? ORACLE_OK : ORACLE_BAD_PATH;
+}
+
+/* ---------------------------------------------------------------------------------------
+ * Draft-tree construction. Section 3.1 adopts the context-aware dynamic draft tree of
+ * EAGLE-2; Appendix A fixes its hyper-parameters (30 draft tokens, depth 3, 8 nodes kept
+ * per expansion). The published procedure, restated:
+ *   - every tree node carries the sum of the draft model's log-probabilities along its
+ *     path from the root (its score; the root has 0);
+ *   - an expansion step takes the current frontier (the root at first, then K nodes),
+ *     gives every frontier node its K most likely next tokens as children (candidates),
+ *     child score = frontier node's score + log softmax(draft logits of that node)[token],
+ *     and keeps the K best-scored of the new candidates as the next frontier;
+ *   - after the last step the N best-scored candidates over all levels are the draft
+ *     tree. A child never scores above its parent, so that set is closed under taking
+ *     parents; among such closed sets of N nodes it has the largest total probability.
+ * The draft model's forward pass is outside this path: its logits are inputs.
+ * ------------------------------------------------------------------------------------ */
+
+/* One expansion step for one sequence.
+ * logits [F][ld] (V used): draft logits at the F frontier nodes; cum_in [F]: their scores.
+ * Candidate f*K + r is the r-th most likely token of frontier node f (larger logit first,
+ * equal logits: lower token id first): cand_token, cand_score = cum_in[f] + logit -
+ * logsumexp(row f). frontier [min(K, F*K)]: the candidates kept for the next step, i.e.
+ * the best by (score descending, candidate index ascending), listed in ascending candidate
+ * index. *cut_gap = score of the worst kept candidate minus score of the best dropped one
+ * (+inf if nothing is dropped): how far the selection is from flipping. */
+int oracle_draft_expand(const float* logits, int64_t ld, int32_t V, const float* cum_in, int32_t F,
+                        int32_t K, int32_t* cand_token, double* cand_score, int32_t* frontier,
+                        double* cut_gap) {
+    if (F < 1 || K < 1 || K > V || K > 64 || F > 64) return ORACLE_BAD_SIZE;
+    unsigned char* taken = (unsigned char*)calloc((size_t)V, 1);
+    if (!taken) return ORACLE_BAD_SIZE;
+    for (int32_t f = 0; f < F; ++f) {
+        const float* row = logits + (int64_t)f * ld;
+        double m = -INFINITY;
+        for (int32_t j = 0; j < V; ++j)
+            if ((double)row[j] > m) m = (double)row[j];
+        double s = 0.0;
+        for (int32_t j = 0; j < V; ++j) s += exp((double)row[j] - m);
+        const double lse = m + log(s);
+        memset(taken, 0, (size_t)V);
+        for (int32_t r = 0; r < K; ++r) {
+            int32_t best = -1;
+            for (int32_t j = 0; j < V; ++j)
+                if (!taken[j] && (best < 0 || row[j] > row[best])) best = j;
+            taken[best] = 1;
+            cand_token[f * K + r] = best;
+            cand_score[f * K + r] = (double)cum_in[f] + ((double)row[best] - lse);
+        }
+    }
+    free(taken);
+    const int32_t C = F * K, keep = K < C ? K : C;
+    unsigned char kept[64 * 64];
+    memset(kept, 0, sizeof kept);
+    double worst_kept = INFINITY;
+    for (int32_t r = 0; r < keep; ++r) {
+        int32_t best = -1;
+        for (int32_t c = 0; c < C; ++c)
+            if (!kept[c] && (best < 0 || cand_score[c] > cand_score[best])) best = c;
+        kept[best] = 1;
+        worst_kept = cand_score[best];
+    }
+    double best_dropped = -INFINITY;
+    int32_t n = 0;
+    for (int32_t c = 0; c < C; ++c) {
+        if (kept[c]) frontier[n++] = c;
+        else if (cand_score[c] > best_dropped) best_dropped = cand_score[c];
+    }
+    *cut_gap = (keep < C) ? worst_kept - best_dropped : INFINITY;
+    return ORACLE_OK;
+}
+
+/* The final selection for one sequence.
+ * M candidates (all levels, in the order they were created): token, score (fp32 as the
+ * caller stores it; compared as such), parent candidate (-1: child of the root, else an
+ * earlier candidate). Picks the min(N, M) best by (score descending, index ascending) and
+ * emits them as a tree in ascending candidate order behind the root (node 0, token
+ * root_token): parent[] / tokens[] / node_cand[] (candidate index of each node, -1 for the
+ * root) of *T_out = picked + 1 nodes. Parents precede children, and levels stay together
+ * when the caller appended candidates level by level.
+ * ORACLE_BAD_PARENT: a cand_parent outside [-1, index), or a picked candidate whose parent
+ * was not picked (only possible when a child scores above its parent: not a sum of
+ * log-probabilities). */
+int oracle_draft_tree_build(const int32_t* cand_token, const float* cand_score, const int32_t* cand_parent,
+                            int32_t M, int32_t N, int32_t root_token, int32_t* parent, int32_t* tokens,
+                            int32_t* node_cand, int32_t* T_out) {
+    if (M < 1 || M > 4096 || N < 1 || N > 63) return ORACLE_BAD_SIZE;
+    for (int32_t c = 0; c < M; ++c)
+        if (cand_parent[c] < -1 || cand_parent[c] >= c) return ORACLE_BAD_PARENT;
+    unsigned char* picked = (unsigned char*)calloc((size_t)M, 1);
+    int32_t* node_of = (int32_t*)malloc((size_t)M * sizeof(int32_t));
+    if (!picked || !node_of) return ORACLE_BAD_SIZE;
+    const int32_t take = N < M ? N : M;
+    for (int32_t r = 0; r < take; ++r) {
+        int32_t best = -1;
+        for (int32_t c = 0; c < M; ++c)
+            if (!picked[c] && (best < 0 || cand_score[c] > cand_score[best])) best = c;
+        picked[best] = 1;
+    }
+    int rc = ORACLE_OK;
+    int32_t t = 0;
+    parent[0] = -1;
+    tokens[0] = root_token;
+    node_cand[0] = -1;
+    for (int32_t c = 0; c < M && rc == ORACLE_OK; ++c) {
+        if (!picked[c]) continue;
+        ++t;
+        node_of[c] = t;
+        const int32_t pc = cand_parent[c];
+        if (pc >= 0 && !picked[pc]) rc = ORACLE_BAD_PARENT;
+        parent[t] = pc < 0 ? 0 : node_of[pc];
+        tokens[t] = cand_token[c];
+        node_cand[t] = c;
+    }
+    *T_out = take + 1;
+    free(picked);
+    free(node_of);
+    return rc;
 }

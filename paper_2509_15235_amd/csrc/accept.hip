@@ -49,7 +49,9 @@ __global__ __launch_bounds__(kArgmaxBlock) void argmax_partial_kernel(const Acce
     Best best = {-INFINITY, INT32_MAX};
     if (p.vec_ok) {
         // chunk_elems = 4 * kArgmaxBlock * kVecPerThread: every thread's loads are issued
-        // before the first compare, ascending index order per thread keeps "first maximum"
+        // before the first compare. The maximum is found on values alone (one v_max per
+        // element); the index is recovered afterwards as the lowest position that equals the
+        // wave's maximum. NaN never equals anything and never survives fmaxf, -0 == +0.
         const int nvec = (end - begin) >> 2;
         const f32x4* __restrict__ lv = (const f32x4*)(lg + begin);
         f32x4 a[kVecPerThread];
@@ -58,15 +60,26 @@ __global__ __launch_bounds__(kArgmaxBlock) void argmax_partial_kernel(const Acce
             const int k = threadIdx.x + j * kArgmaxBlock;
             a[j] = (k < nvec) ? __builtin_nontemporal_load(lv + k) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         }
+        float m = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < kVecPerThread; ++j) {
+        for (int j = 0; j < kVecPerThread; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) m = fmaxf(m, a[j][e]);
+        for (int t = begin + 4 * nvec + threadIdx.x; t < end; t += kArgmaxBlock) m = fmaxf(m, lg[t]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+        int32_t idx = INT32_MAX;
+        for (int t = begin + 4 * nvec + threadIdx.x; t < end; t += kArgmaxBlock)
+            if (lg[t] == m) idx = min(idx, t);
+#pragma unroll
+        for (int j = kVecPerThread - 1; j >= 0; --j) {
             const int k = threadIdx.x + j * kArgmaxBlock;
-            if (k < nvec) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) take(best, a[j][e], begin + 4 * k + e);
-            }
+            for (int e = 3; e >= 0; --e)
+                if (k < nvec && a[j][e] == m) idx = begin + 4 * k + e;
         }
-        for (int t = begin + 4 * nvec + threadIdx.x; t < end; t += kArgmaxBlock) take(best, lg[t], t);
+        best.v = m;       // the wave's maximum; lanes without it keep INT32_MAX and lose the tie
+        best.i = idx;
     } else {
         for (int t = begin + threadIdx.x; t < end; t += kArgmaxBlock) take(best, lg[t], t);
     }
