@@ -14,6 +14,9 @@
  *                             bonus token (Section 3.1 at temperature 0)
  *   vs_tree_accept_sample     the same walk at a temperature > 0: accept with probability
  *                             min(1, p/p_hat), residual resampling (Section 3.1)
+ *   vs_draft_expand /         builds the draft tree that the next step verifies: top-K
+ *   vs_draft_tree_build       expansion scored by cumulative log-probability, best-N selection
+ *                             (Section 3.1's dynamic draft tree, Appendix A's parameters)
  *   vs_tree_kv_commit         keeps the accepted path's K/V rows, in order, behind the
  *                             prefix of the pre-allocated cache (Section 3.1, Appendix A)
  *
@@ -65,7 +68,9 @@ typedef enum vs_status {
     VS_STATUS_BAD_PARENT = 2, /* some parent[i], i >= 1, outside [0, i) */
     VS_STATUS_BAD_PREFIX = 3, /* prefix_len < 0, > max_prefix_len, or prefix_len + T beyond the cache */
     VS_STATUS_BAD_BLOCK = 4,  /* a block-table entry in use lies outside [0, num_blocks) */
-    VS_STATUS_BAD_PATH = 5    /* accepted_len outside [0, T) or path not 0 followed by increasing node ids */
+    VS_STATUS_BAD_PATH = 5,   /* accepted_len outside [0, T) or path not 0 followed by increasing node ids */
+    VS_STATUS_BAD_CANDIDATE = 6 /* draft tree: cand_parent outside [-1, index), or a selected candidate whose
+                                   parent was not selected (a child scoring above its parent) */
 } vs_status;
 
 typedef enum vs_dtype { VS_BF16 = 0, VS_F32 = 1 } vs_dtype;
@@ -243,6 +248,57 @@ int32_t vs_tree_accept_sample(const float* logits, int64_t ld_logits, int32_t V,
                               int32_t* accepted_len, int32_t* path, int32_t* bonus_token,
                               int32_t* status, void* workspace, size_t workspace_bytes,
                               void* stream);
+
+/*
+ * Draft-tree construction (Section 3.1: the context-aware dynamic draft tree of EAGLE-2;
+ * Appendix A: N = 30 draft tokens, depth 3, K = 8 nodes kept per expansion). A candidate's
+ * score is the sum of the draft model's log-probabilities on its path from the root. The draft
+ * model itself is not part of this library: the caller runs it on the current frontier and
+ * passes its logits. Candidates of all levels live in three caller-owned arrays
+ * cand_token / cand_score / cand_parent of cand_capacity entries per sequence.
+ *
+ * vs_draft_expand, one expansion step:
+ *   logits        [B,F,ld_logits] fp32 in; row (b,f) = draft logits at frontier node f; no NaN;
+ *                 1 <= F <= 64, 1 <= K <= 16, F*K <= 1024, K <= V <= ld_logits
+ *   cum_in        [B,F] fp32 in, scores of the frontier nodes; NULL = all 0 (the root)
+ *   frontier_cand [B,F] int32 in, candidate index of each frontier node; NULL = all -1 (the root)
+ *   cand_base     where this step's F*K candidates go: candidate cand_base + f*K + r is the r-th
+ *                 most likely token of frontier node f (larger logit first, equal logits: lower
+ *                 token id first); cand_base + F*K <= cand_capacity
+ *   cand_token / cand_score / cand_parent  [B,cand_capacity] out at those positions:
+ *                 token id; cum_in + logit - logsumexp(row); frontier_cand of the node
+ *   next_frontier_cand [B,min(K,F*K)] int32 out: the step's best candidates by (score descending,
+ *                 index ascending), listed in ascending candidate index
+ *   next_cum      [B,min(K,F*K)] fp32 out: their scores (the next step's cum_in)
+ *   workspace     at least vs_draft_expand_workspace_bytes(B,F,V,K) bytes, 256-byte aligned
+ * Tokens are exact; scores are fp32 (log-sum-exp over 4096-entry chunks), so two candidates
+ * whose exact scores differ by less than ~1e-5 may swap places at the cut.
+ *
+ * vs_draft_tree_build, the final selection over the first M candidates (1 <= M <= 2048,
+ * 1 <= N <= 63; scores without NaN): the min(N, M) best by (score descending, index ascending)
+ * become nodes 1.. in ascending candidate order behind the root (node 0). With candidates
+ * appended level by level that is level order, and a parent always precedes its children.
+ *   root_token    [B] int32 in or NULL (then draft_tokens[b][0] = -1)
+ *   parent        [B,N+1] int32 out, the tree_parent array of the verification calls
+ *   draft_tokens  [B,N+1] int32 out
+ *   node_cand     [B,N+1] int32 out, candidate index of every node (-1 for the root)
+ *   num_nodes     [B] int32 out: min(N, M) + 1; entries beyond it are -1; 0 on a bad status
+ *   status        [B] int32 out, optional: VS_STATUS_BAD_CANDIDATE if a cand_parent is not in
+ *                 [-1, own index) or the selection is not closed under taking parents
+ */
+size_t vs_draft_expand_workspace_bytes(int32_t B, int32_t F, int32_t V, int32_t K); /* 0 for unsupported sizes */
+
+int32_t vs_draft_expand(const float* logits, int64_t ld_logits, int32_t V, const float* cum_in,
+                        const int32_t* frontier_cand, int32_t B, int32_t F, int32_t K,
+                        int32_t cand_base, int32_t cand_capacity, int32_t* cand_token,
+                        float* cand_score, int32_t* cand_parent, int32_t* next_frontier_cand,
+                        float* next_cum, void* workspace, size_t workspace_bytes, void* stream);
+
+int32_t vs_draft_tree_build(const int32_t* cand_token, const float* cand_score,
+                            const int32_t* cand_parent, int32_t B, int32_t M, int32_t cand_capacity,
+                            int32_t N, const int32_t* root_token, int32_t* parent,
+                            int32_t* draft_tokens, int32_t* node_cand, int32_t* num_nodes,
+                            int32_t* status, void* stream);
 
 /*
  * KV caches of one or more layers that share a layout (host struct, read during the call).

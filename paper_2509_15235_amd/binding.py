@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "vs_version", "vs_strerror", "vs_status_string", "vs_tree_validate_host", "vs_tree_mask_build",
     "vs_attention_plan", "vs_attention_workspace_bytes", "vs_tree_verify_attention",
     "vs_accept_workspace_bytes", "vs_tree_accept", "vs_accept_sample_workspace_bytes", "vs_tree_accept_sample",
-    "vs_tree_kv_commit",
+    "vs_draft_expand_workspace_bytes", "vs_draft_expand", "vs_draft_tree_build", "vs_tree_kv_commit",
 ]
 
 
@@ -99,6 +99,12 @@ def lib():
         L.vs_tree_accept_sample.argtypes = [vp, i64, i32, ctypes.c_float, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp,
                                             sz, vp]
         L.vs_tree_accept_sample.restype = i32
+        L.vs_draft_expand_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.vs_draft_expand_workspace_bytes.restype = sz
+        L.vs_draft_expand.argtypes = [vp, i64, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_draft_expand.restype = i32
+        L.vs_draft_tree_build.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.vs_draft_tree_build.restype = i32
         L.vs_tree_kv_commit.argtypes = [ctypes.POINTER(KVDesc), vp, vp, vp, vp, vp, vp, vp, vp]
         L.vs_tree_kv_commit.restype = i32
         _lib = L
@@ -178,6 +184,26 @@ def vs_tree_accept_sample(logits, ld_logits, V, temperature, draft_tokens, paren
                                        _ptr(u_accept), _ptr(u_bonus), B, T, _ptr(accepted_len), _ptr(path),
                                        _ptr(bonus_token), _ptr(status), _ptr(workspace), workspace_bytes,
                                        _ptr(stream))
+
+
+def vs_draft_expand_workspace_bytes(B: int, F: int, V: int, K: int) -> int:
+    return lib().vs_draft_expand_workspace_bytes(B, F, V, K)
+
+
+def vs_draft_expand(logits, ld_logits, V, cum_in, frontier_cand, B, F, K, cand_base, cand_capacity, cand_token,
+                    cand_score, cand_parent, next_frontier_cand, next_cum, workspace=None, workspace_bytes=0,
+                    stream=None) -> int:
+    return lib().vs_draft_expand(_ptr(logits), ld_logits, V, _ptr(cum_in), _ptr(frontier_cand), B, F, K, cand_base,
+                                 cand_capacity, _ptr(cand_token), _ptr(cand_score), _ptr(cand_parent),
+                                 _ptr(next_frontier_cand), _ptr(next_cum), _ptr(workspace), workspace_bytes,
+                                 _ptr(stream))
+
+
+def vs_draft_tree_build(cand_token, cand_score, cand_parent, B, M, cand_capacity, N, root_token, parent,
+                        draft_tokens, node_cand, num_nodes, status=None, stream=None) -> int:
+    return lib().vs_draft_tree_build(_ptr(cand_token), _ptr(cand_score), _ptr(cand_parent), B, M, cand_capacity, N,
+                                     _ptr(root_token), _ptr(parent), _ptr(draft_tokens), _ptr(node_cand),
+                                     _ptr(num_nodes), _ptr(status), _ptr(stream))
 
 
 def vs_tree_kv_commit(desc: KVDesc, k_cache, v_cache, prefix_len, path, accepted_len, new_prefix_len,

@@ -204,6 +204,7 @@ const char* vs_status_string(int32_t code) {
     case VS_STATUS_BAD_PREFIX: return "prefix_len outside the cache or the host bound";
     case VS_STATUS_BAD_BLOCK: return "a block-table entry is outside the pool";
     case VS_STATUS_BAD_PATH: return "accepted path is not the root followed by increasing node ids";
+    case VS_STATUS_BAD_CANDIDATE: return "a candidate's parent is not an earlier candidate, or a child outscores its parent";
     default: return "unknown status";
     }
 }
@@ -388,6 +389,78 @@ int32_t vs_tree_accept_sample(const float* logits, int64_t ld_logits, int32_t V,
     p.part_m = (float*)workspace;
     p.part_s = (float*)((char*)workspace + align_up(n * sizeof(float)));
     return launch_accept_sample(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
+}
+
+size_t vs_draft_expand_workspace_bytes(int32_t B, int32_t F, int32_t V, int32_t K) {
+    if (B < 1 || F < 1 || F > VS_MAX_TREE || K < 1 || K > kMaxDraftK || F * K > kMaxDraftCand || V < K) return 0;
+    const size_t n = (size_t)B * F * accept_chunks(V);
+    return 2 * align_up(n * sizeof(float)) + 2 * align_up(n * K * sizeof(float));
+}
+
+int32_t vs_draft_expand(const float* logits, int64_t ld_logits, int32_t V, const float* cum_in,
+                        const int32_t* frontier_cand, int32_t B, int32_t F, int32_t K, int32_t cand_base,
+                        int32_t cand_capacity, int32_t* cand_token, float* cand_score, int32_t* cand_parent,
+                        int32_t* next_frontier_cand, float* next_cum, void* workspace, size_t workspace_bytes_given,
+                        void* stream) {
+    if (!logits || !cand_token || !cand_score || !cand_parent || !next_frontier_cand || !next_cum) return VS_ERR_NULL;
+    if (B < 1 || F < 1 || F > VS_MAX_TREE || K < 1 || K > kMaxDraftK || F * K > kMaxDraftCand) return VS_ERR_SHAPE;
+    if (V < K || ld_logits < V) return VS_ERR_SHAPE;
+    if (cand_base < 0 || cand_capacity < 1 || (int64_t)cand_base + (int64_t)F * K > cand_capacity) return VS_ERR_SHAPE;
+    const size_t need = vs_draft_expand_workspace_bytes(B, F, V, K);
+    if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;
+    DraftExpandParams p{};
+    p.logits = logits;
+    p.ld = ld_logits;
+    p.V = V;
+    p.cum_in = cum_in;
+    p.frontier_cand = frontier_cand;
+    p.B = B;
+    p.F = F;
+    p.K = K;
+    p.cand_base = cand_base;
+    p.cand_capacity = cand_capacity;
+    p.cand_token = cand_token;
+    p.cand_score = cand_score;
+    p.cand_parent = cand_parent;
+    p.next_frontier_cand = next_frontier_cand;
+    p.next_cum = next_cum;
+    p.chunks = accept_chunks(V);
+    p.chunk_elems = kArgmaxChunk;
+    p.vec_ok = (aligned16(logits) && ld_logits % 4 == 0) ? 1 : 0;
+    const size_t n = (size_t)B * F * p.chunks;
+    char* w = (char*)workspace;
+    p.part_m = (float*)w;
+    w += align_up(n * sizeof(float));
+    p.part_s = (float*)w;
+    w += align_up(n * sizeof(float));
+    p.part_tv = (float*)w;
+    w += align_up(n * K * sizeof(float));
+    p.part_ti = (int32_t*)w;
+    return launch_draft_expand(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
+}
+
+int32_t vs_draft_tree_build(const int32_t* cand_token, const float* cand_score, const int32_t* cand_parent, int32_t B,
+                            int32_t M, int32_t cand_capacity, int32_t N, const int32_t* root_token, int32_t* parent,
+                            int32_t* draft_tokens, int32_t* node_cand, int32_t* num_nodes, int32_t* status,
+                            void* stream) {
+    if (!cand_token || !cand_score || !cand_parent || !parent || !draft_tokens || !node_cand || !num_nodes)
+        return VS_ERR_NULL;
+    if (B < 1 || M < 1 || M > kMaxDraftTotal || cand_capacity < M || N < 1 || N > VS_MAX_TREE - 1) return VS_ERR_SHAPE;
+    DraftBuildParams p{};
+    p.cand_token = cand_token;
+    p.cand_score = cand_score;
+    p.cand_parent = cand_parent;
+    p.root_token = root_token;
+    p.B = B;
+    p.M = M;
+    p.N = N;
+    p.cand_capacity = cand_capacity;
+    p.parent = parent;
+    p.tokens = draft_tokens;
+    p.node_cand = node_cand;
+    p.num_nodes = num_nodes;
+    p.status = status;
+    return launch_draft_tree_build(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
 }
 
 int32_t vs_tree_kv_commit(const vs_kv_desc* d, void* k_cache, void* v_cache, const int32_t* prefix_len,

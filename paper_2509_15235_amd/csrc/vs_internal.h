@@ -86,6 +86,43 @@ struct SampleParams {
     int32_t vec_ok;        // rows are 16-byte aligned → float4 loads
 };
 
+constexpr int kMaxDraftK = 16;        // children per frontier node
+constexpr int kMaxDraftCand = 1024;   // F * K candidates of one expansion step
+constexpr int kMaxDraftTotal = 2048;  // candidates of all levels at the final selection
+
+struct DraftExpandParams {
+    const float* logits;          // [B*F][ld]
+    int64_t ld;
+    int32_t V;
+    const float* cum_in;          // [B*F], may be null (all 0)
+    const int32_t* frontier_cand; // [B*F], may be null (all -1: the root)
+    int32_t B, F, K;
+    int32_t cand_base, cand_capacity;
+    int32_t* cand_token;          // [B][cand_capacity]
+    float* cand_score;
+    int32_t* cand_parent;
+    int32_t* next_frontier_cand;  // [B][min(K, F*K)]
+    float* next_cum;
+    float* part_m;                // [B*F][chunks]
+    float* part_s;
+    float* part_tv;               // [B*F][chunks][K]
+    int32_t* part_ti;
+    int32_t chunks, chunk_elems, vec_ok;
+};
+
+struct DraftBuildParams {
+    const int32_t* cand_token;    // [B][cand_capacity]
+    const float* cand_score;
+    const int32_t* cand_parent;
+    const int32_t* root_token;    // [B], may be null
+    int32_t B, M, N, cand_capacity;
+    int32_t* parent;              // [B][N+1]
+    int32_t* tokens;
+    int32_t* node_cand;
+    int32_t* num_nodes;           // [B]
+    int32_t* status;              // may be null
+};
+
 struct CommitParams {
     void* k;
     void* v;
@@ -121,6 +158,8 @@ hipError_t launch_attention_mfma_pipe(const AttnParams& p, int rpw, int waves, h
 hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_accept_sample(const SampleParams& p, hipStream_t s);
+hipError_t launch_draft_expand(const DraftExpandParams& p, hipStream_t s);
+hipError_t launch_draft_tree_build(const DraftBuildParams& p, hipStream_t s);
 hipError_t launch_kv_commit(const CommitParams& p, hipStream_t s);
 
 } // namespace vs

@@ -154,6 +154,55 @@ def run_accept_sample(logits: np.ndarray, tokens: np.ndarray, parent: np.ndarray
     return alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy(), status.cpu().numpy()
 
 
+class DeviceDraft:
+    """Candidate arrays of B sequences on the device plus the calls that fill them."""
+
+    def __init__(self, B, K, capacity):
+        self.B, self.K, self.cap = B, K, capacity
+        self.tok = torch.full((B, capacity), -7, device="cuda", dtype=torch.int32)
+        self.score = torch.full((B, capacity), float("nan"), device="cuda", dtype=torch.float32)
+        self.par = torch.full((B, capacity), -7, device="cuda", dtype=torch.int32)
+        self.M = 0
+
+    def expand(self, logits: np.ndarray, cum_in, frontier_cand, ld=None, offset_elems=0):
+        """logits [B,F,V] numpy; cum_in / frontier_cand device tensors [B,F] or None.
+        Returns device tensors (next_frontier_cand [B,keep], next_cum [B,keep])."""
+        B, F, V = logits.shape
+        K = self.K
+        ld = V if ld is None else ld
+        buf = torch.full((B * F * ld + offset_elems + 8,), float("nan"), device="cuda", dtype=torch.float32)
+        view = buf[offset_elems:offset_elems + B * F * ld].view(B * F, ld)
+        view[:, :V] = dev(logits.reshape(B * F, V))
+        keep = min(K, F * K)
+        nf = torch.full((B, keep), -7, device="cuda", dtype=torch.int32)
+        nc = torch.full((B, keep), float("nan"), device="cuda", dtype=torch.float32)
+        nbytes = vs.vs_draft_expand_workspace_bytes(B, F, V, K)
+        assert nbytes > 0
+        ws = torch.empty(nbytes, device="cuda", dtype=torch.uint8)
+        rc = vs.vs_draft_expand(view.data_ptr(), ld, V, cum_in, frontier_cand, B, F, K, self.M, self.cap, self.tok,
+                                self.score, self.par, nf, nc, ws, nbytes, stream_ptr())
+        assert rc == 0, vs.vs_strerror(rc)
+        torch.cuda.synchronize()
+        self.M += F * K
+        return nf, nc
+
+    def build(self, N, root_token=None, M=None):
+        B = self.B
+        M = self.M if M is None else M
+        parent = torch.full((B, N + 1), -7, device="cuda", dtype=torch.int32)
+        tokens = torch.full((B, N + 1), -7, device="cuda", dtype=torch.int32)
+        node_cand = torch.full((B, N + 1), -7, device="cuda", dtype=torch.int32)
+        num = torch.full((B,), -7, device="cuda", dtype=torch.int32)
+        status = torch.full((B,), -99, device="cuda", dtype=torch.int32)
+        rt = None if root_token is None else dev(np.asarray(root_token, dtype=np.int32))
+        rc = vs.vs_draft_tree_build(self.tok, self.score, self.par, B, M, self.cap, N, rt, parent, tokens, node_cand,
+                                    num, status, stream_ptr())
+        assert rc == 0, vs.vs_strerror(rc)
+        torch.cuda.synchronize()
+        return (parent.cpu().numpy(), tokens.cpu().numpy(), node_cand.cpu().numpy(), num.cpu().numpy(),
+                status.cpu().numpy())
+
+
 class DeviceCommit:
     """Device copies of L layers of K/V caches (stacked along a leading layer axis) plus the
     descriptor of vs_tree_kv_commit. `k_layers` / `v_layers`: numpy [L, ...one layer's cache...]

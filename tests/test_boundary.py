@@ -171,6 +171,30 @@ def test_accept_sample_rejects_bad_arguments_before_any_launch():
     assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, g, g, 1, 4, g, g, g, None, g + 8, 1 << 20) == -4
 
 
+def test_draft_calls_reject_bad_arguments_before_any_launch():
+    g = 4096  # never dereferenced
+    assert vs.vs_draft_expand_workspace_bytes(1, 8, 152064, 8) >= 8 * 38 * (8 + 8 * 8)
+    assert vs.vs_draft_expand_workspace_bytes(1, 8, 152064, 17) == 0
+    assert vs.vs_draft_expand_workspace_bytes(1, 65, 152064, 8) == 0
+    assert vs.vs_draft_expand_workspace_bytes(1, 1, 4, 8) == 0                   # K > V
+    ws = dict(workspace=g, workspace_bytes=1 << 24)
+    ex = lambda **kw: vs.vs_draft_expand(**{**dict(logits=g, ld_logits=100, V=100, cum_in=None, frontier_cand=None,
+                                                  B=1, F=1, K=8, cand_base=0, cand_capacity=136, cand_token=g,
+                                                  cand_score=g, cand_parent=g, next_frontier_cand=g, next_cum=g,
+                                                  **ws), **kw})
+    assert ex(logits=None) == -1 and ex(cand_score=None) == -1 and ex(next_cum=None) == -1
+    assert ex(K=0) == -2 and ex(K=17) == -2 and ex(F=0) == -2 and ex(F=65) == -2 and ex(V=7) == -2
+    assert ex(ld_logits=99) == -2
+    assert ex(cand_base=130) == -2 and ex(cand_base=-1) == -2 and ex(F=8, cand_base=73) == -2
+    assert ex(workspace=None) == -4 and ex(workspace_bytes=64) == -4 and ex(workspace=g + 16) == -4
+    bd = lambda **kw: vs.vs_draft_tree_build(**{**dict(cand_token=g, cand_score=g, cand_parent=g, B=1, M=136,
+                                                      cand_capacity=136, N=30, root_token=None, parent=g,
+                                                      draft_tokens=g, node_cand=g, num_nodes=g), **kw})
+    assert bd(cand_token=None) == -1 and bd(num_nodes=None) == -1
+    assert bd(M=0) == -2 and bd(M=2049, cand_capacity=4096) == -2 and bd(M=137) == -2
+    assert bd(N=0) == -2 and bd(N=64) == -2 and bd(B=0) == -2
+
+
 def test_kv_commit_rejects_bad_arguments_before_any_launch():
     def kd(**kw):
         d = vs.KVDesc(B=2, T=8, Hkv=2, d=64, dtype=vs.VS_BF16, num_layers=3, stride_layer=2 * 2 * 100 * 64,
