@@ -160,6 +160,46 @@ def main():
         check(vs.vs_tree_accept(st["logits"], V, V, tokens, parent1, 1, T, alen, path, bonus, amax, status,
                                 aws, aws_bytes, stream))
 
+    # stochastic acceptance (temperature 1) and draft-tree construction (Appendix A: K = 8, depth 3, N = 30):
+    # the rows built beyond the greedy step; timed separately, not part of `value`
+    ua_h, ub_h = gen.uniforms(args.seed, 1, T)
+    u_acc, u_bon = torch.from_numpy(ua_h).to(dev), torch.from_numpy(ub_h).to(dev)
+    sws_bytes = vs.vs_accept_sample_workspace_bytes(1, T, V)
+    sws = torch.empty(sws_bytes, device=dev, dtype=torch.uint8)
+    s_alen, s_path, s_bonus = torch.zeros_like(alen), torch.zeros_like(path), torch.zeros_like(bonus)
+
+    def enqueue_sample(st, stream):
+        check(vs.vs_tree_accept_sample(st["logits"], V, V, 1.0, tokens, parent1, u_acc, u_bon, 1, T, s_alen, s_path,
+                                       s_bonus, status, sws, sws_bytes, stream))
+
+    DK, DD, DN = 8, 3, 30
+    dcap = DK + (DD - 1) * DK * DK
+    d_tok = torch.zeros((1, dcap), device=dev, dtype=torch.int32)
+    d_par = torch.zeros((1, dcap), device=dev, dtype=torch.int32)
+    d_score = torch.zeros((1, dcap), device=dev, dtype=torch.float32)
+    d_front = [torch.zeros((1, DK), device=dev, dtype=torch.int32) for _ in range(DD)]
+    d_cum = [torch.zeros((1, DK), device=dev, dtype=torch.float32) for _ in range(DD)]
+    d_parent = torch.zeros((1, DN + 1), device=dev, dtype=torch.int32)
+    d_tokens, d_cand = torch.zeros_like(d_parent), torch.zeros_like(d_parent)
+    d_num = torch.zeros((1,), device=dev, dtype=torch.int32)
+    dws_bytes = vs.vs_draft_expand_workspace_bytes(1, DK, V, DK)
+    dws = torch.empty(dws_bytes, device=dev, dtype=torch.uint8)
+    draft_rows = 1 + (DD - 1) * DK                                                        # logits rows one tree reads
+
+    def enqueue_draft(st, stream):
+        # the target's logits rows stand in for the draft model's (same shape and distribution)
+        lg = st["logits"].data_ptr()
+        row, base = 0, 0
+        for level in range(DD):
+            F = 1 if level == 0 else DK
+            check(vs.vs_draft_expand(lg + row * V * 4, V, V, None if level == 0 else d_cum[level - 1],
+                                     None if level == 0 else d_front[level - 1], 1, F, DK, base, dcap, d_tok, d_score,
+                                     d_par, d_front[level], d_cum[level], dws, dws_bytes, stream))
+            row += F
+            base += F * DK
+        check(vs.vs_draft_tree_build(d_tok, d_score, d_par, 1, dcap, dcap, DN, None, d_parent, d_tokens, d_cand, d_num,
+                                     status, stream))
+
     stream = torch.cuda.Stream(device=dev)
     sp = stream.cuda_stream
     check(vs.vs_tree_mask_build(parentL, L, T, maskL, depth, status, sp))
@@ -187,9 +227,26 @@ def main():
             want = getattr(host_layers[l], bits)[0].copy()
             oracle.kv_commit_seq(want, S, o_path[0], int(o_alen[0]))
             commit_ok = commit_ok and bool(np.array_equal(got[l], want))
-    if not (err0 <= 2e-2 and accept_ok and commit_ok):
-        print(f"bench.py: parity check failed (attention max|err| {err0}, accept ok {accept_ok}, commit ok {commit_ok})",
-              file=sys.stderr)
+    # stochastic acceptance: the GPU's outcome must be one the rule allows within the fp32 error bound
+    with torch.cuda.stream(stream):
+        enqueue_sample(sets[0], sp)
+        enqueue_draft(sets[0], sp)
+    stream.synchronize()
+    rc_s, _ = oracle.tree_accept_sample_check_seq(acc_h.logits[0], acc_h.tokens[0], acc_h.parent[0], 1.0,
+                                                  ua_h[0].astype(np.float64), float(ub_h[0]), int(s_alen.item()),
+                                                  s_path.cpu().numpy()[0], int(s_bonus.item()), 2e-5)
+    sample_ok = rc_s == 0
+    # draft tree: the final selection, bit for bit, from the candidates the GPU produced; first level against the oracle
+    rc_d, o_par, o_tok, o_cand = oracle.draft_tree_build_seq(d_tok.cpu().numpy()[0], d_score.cpu().numpy()[0],
+                                                             d_par.cpu().numpy()[0], DN)
+    rc_e, e_tok, e_sc, _, _ = oracle.draft_expand_seq(acc_h.logits[0][:1], np.zeros(1, np.float32), DK)
+    draft_ok = bool(rc_d == 0 and rc_e == 0 and int(d_num.item()) == DN + 1
+                    and (d_parent.cpu().numpy()[0] == o_par).all() and (d_tokens.cpu().numpy()[0] == o_tok).all()
+                    and (d_tok.cpu().numpy()[0, :DK] == e_tok).all()
+                    and np.abs(d_score.cpu().numpy()[0, :DK] - e_sc).max() <= 3e-5)
+    if not (err0 <= 2e-2 and accept_ok and commit_ok and sample_ok and draft_ok):
+        print(f"bench.py: parity check failed (attention max|err| {err0}, accept ok {accept_ok}, commit ok {commit_ok}, "
+              f"sample ok {sample_ok}, draft ok {draft_ok})", file=sys.stderr)
         sys.exit(4)
 
     # ---------------------------------------------------------------- runners (HIP graphs or eager)
@@ -226,26 +283,25 @@ def main():
     ms_step, ms_step_wall = timed(step_runner, args.steps, args.warmup)
     ms_step = max(ms_step, ms_step_wall) if args.no_graph else ms_step
 
-    # the roofline launch: one graph holds one folded call per buffer set, back to back, so that
-    # the event time per call is the kernel's duration and not the gap between graph launches
-    def enqueue_folded_all(_st, stream_):
-        for st in sets:
-            enqueue_folded(st, stream_)
-    folded_runner = build_runner(enqueue_folded_all)
-    ms_folded, _ = timed(folded_runner, max(args.steps // 4, 12), 3)
-    ms_folded /= nsets
+    # kernel-level legs: one graph holds one call per buffer set, back to back, so that the event
+    # time per call is the duration of the call's kernels and not the gap between graph launches
+    def per_call(enq, iters, warmup):
+        def enqueue_all(_st, stream_):
+            for st in sets:
+                enq(st, stream_)
+        ms, _ = timed(build_runner(enqueue_all), iters, warmup)
+        return ms / nsets
+
+    ms_folded = per_call(enqueue_folded, max(args.steps // 4, 12), 3)
 
     def enqueue_one_layer(st, stream_):
         check(vs.vs_tree_verify_attention(desc1, st["q"], st["k"], st["v"], prefix1, parent1, mask, st["out"],
                                           status, ws, ws_bytes, stream_))
-    single_runner = build_runner(enqueue_one_layer)
-    ms_single, _ = timed(single_runner, max(args.steps, 50) * 4, max(args.warmup, 5))
-
-    accept_runner = build_runner(enqueue_accept)
-    ms_accept, _ = timed(accept_runner, max(args.steps, 50), max(args.warmup, 5))
-
-    commit_runner = build_runner(enqueue_commit)
-    ms_commit, _ = timed(commit_runner, max(args.steps, 50), max(args.warmup, 5))
+    ms_single = per_call(enqueue_one_layer, max(args.steps, 50), max(args.warmup, 5))
+    ms_accept = per_call(enqueue_accept, max(args.steps // 2, 25), max(args.warmup, 5))
+    ms_sample = per_call(enqueue_sample, max(args.steps // 2, 25), max(args.warmup, 5))
+    ms_draft = per_call(enqueue_draft, max(args.steps // 2, 25), max(args.warmup, 5))
+    ms_commit = per_call(enqueue_commit, max(args.steps // 2, 25), max(args.warmup, 5))
 
     # a plain device copy of known size: the reference that scales rocprofv3's FETCH_SIZE /
     # WRITE_SIZE counters when HBM traffic of the kernels above is derived from a --pmc run
@@ -298,7 +354,17 @@ def main():
     argmax_gbs = logit_bytes / (ms_accept * 1e-3) / 1e9
     argmax = {"bound": "hbm", "achieved": round(argmax_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
               "frac": round(argmax_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(ms_accept * 1e3, 2),
-              "bytes": logit_bytes}
+              "bytes": logit_bytes, "note": "whole vs_tree_accept call: logits scan + tree walk (two dependent kernels)"}
+
+    sample_gbs = logit_bytes / (ms_sample * 1e-3) / 1e9
+    sample = {"bound": "hbm", "achieved": round(sample_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+              "frac": round(sample_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(ms_sample * 1e3, 2),
+              "bytes": logit_bytes, "note": "vs_tree_accept_sample at temperature 1 (scan + walk); not part of the step"}
+    draft_bytes = draft_rows * V * 4
+    draft = {"bound": "latency", "us_per_tree": round(ms_draft * 1e3, 2), "bytes": draft_bytes,
+             "gbs": round(draft_bytes / (ms_draft * 1e-3) / 1e9, 1),
+             "note": f"{DD} x vs_draft_expand (K={DK}) + vs_draft_tree_build (N={DN}) = 7 dependent kernels over "
+                     f"{draft_rows} logits rows; the draft model between the expansions is not included"}
 
     commit_bytes = 2 * 2 * L * Hkv * int(o_alen[0]) * d * eb                               # rows read + rows written, K and V
     commit = {"bound": "latency", "us_per_launch": round(ms_commit * 1e3, 2), "accepted_len": int(o_alen[0]),
@@ -324,8 +390,9 @@ def main():
         "config": {"workload": f"{cfg.name}: B=1 Hq={Hq} Hkv={Hkv} d={d} prefix={S} tree={T} nodes depth<={cfg.max_depth} "
                                f"layers={L} vocab={V}; step = mask_build + {L} x attention + accept",
                    "hip_graph": not args.no_graph, "buffer_sets": nsets},
-        "roofline": roofline, "per_layer_call": per_layer, "argmax": argmax, "kv_commit": commit, "cpu_baseline": cpu,
-        "parity": {"attention_max_abs_err_layer0": err0, "accept_bit_exact": accept_ok, "commit_bit_exact": commit_ok},
+        "roofline": roofline, "per_layer_call": per_layer, "argmax": argmax, "accept_sample": sample, "draft_tree": draft, "kv_commit": commit, "cpu_baseline": cpu,
+        "parity": {"attention_max_abs_err_layer0": err0, "accept_bit_exact": accept_ok, "commit_bit_exact": commit_ok,
+                   "sample_outcome_valid": sample_ok, "draft_tree_bit_exact": draft_ok},
     }
     print(json.dumps(line))
 

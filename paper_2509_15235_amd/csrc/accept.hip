@@ -105,6 +105,7 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
     __shared__ int32_t sflag;
     __shared__ int32_t samax[VS_MAX_TREE];
     __shared__ int32_t spath[VS_MAX_TREE];
+    __shared__ int32_t sdraft[VS_MAX_TREE];
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = p.T;
@@ -114,11 +115,29 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
     {
         const int i = tid >> 2, sub = tid & 3;
         Best best = {-INFINITY, INT32_MAX};
-        if (i < T) {
+        // requested now, used after the merge: the row's first logit (NaN rule) and the draft tokens
+        const float first = (i < T && sub == 0) ? p.logits[((int64_t)b * T + i) * p.ld] : 0.f;
+        if (tid < T) sdraft[tid] = p.draft[(int64_t)b * T + tid];
+        {
+            // sixteen chunk results per thread are requested before the first compare: one memory
+            // round trip for vocabularies up to 64 chunks
+            constexpr int kPre = 16;
             const int64_t row = (int64_t)b * T + i;
             const float* pv = p.part_val + row * p.chunks;
             const int32_t* pi = p.part_idx + row * p.chunks;
-            for (int c = sub; c < p.chunks; c += 4) take(best, pv[c], pi[c]);
+            for (int c0 = sub; c0 < p.chunks; c0 += 4 * kPre) {
+                float v[kPre];
+                int32_t x[kPre];
+#pragma unroll
+                for (int q = 0; q < kPre; ++q) {
+                    const int c = c0 + 4 * q;
+                    const bool ok = i < T && c < p.chunks;
+                    v[q] = ok ? pv[c] : -INFINITY;
+                    x[q] = ok ? pi[c] : INT32_MAX;
+                }
+#pragma unroll
+                for (int q = 0; q < kPre; ++q) take(best, v[q], x[q]);
+            }
         }
 #pragma unroll
         for (int o = 1; o <= 2; o <<= 1) {
@@ -130,7 +149,6 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
             // what a left-to-right '>' scan returns: a NaN in column 0 is never displaced,
             // and a row with nothing above -inf keeps index 0
             const int64_t row = (int64_t)b * T + i;
-            const float first = p.logits[row * p.ld];
             int32_t idx = best.i;
             if (first != first || idx == INT32_MAX) idx = 0;
             samax[i] = idx;
@@ -149,7 +167,7 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
             int j = lane;
             while (j > 0) {
                 const int pj = sp[j];
-                ok = ok && (p.draft[(int64_t)b * T + j] == samax[pj]);
+                ok = ok && (sdraft[j] == samax[pj]);
                 j = pj;
                 ++dep;
             }

@@ -81,32 +81,79 @@ __global__ __launch_bounds__(kArgmaxBlock) void softmax_stats_partial_kernel(con
 
 // grid = B, block = 256. Every thread runs the (short, sequential) walk on the same LDS
 // data, so its branches are uniform and the whole workgroup can turn to a chunk-wide pass
-// when one is needed.
+// when one is needed. Everything the walk compares is fetched up front (row maxima and
+// masses, the uniforms, every candidate's weight in its parent's row), so a step of the walk
+// costs no memory round trip: removing a rejected token just lowers the row's mass. Only when
+// that subtraction would cancel (the rejected token held > 95 % of the mass), and once at the
+// end for the bonus draw, the row's per-chunk masses are brought into LDS.
 __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const SampleParams p) {
     __shared__ int32_t sp[VS_MAX_TREE];
     __shared__ int32_t sflag;
     __shared__ float sM[VS_MAX_TREE];      // row maxima
+    __shared__ float sZ[VS_MAX_TREE];      // row masses relative to the maxima
     __shared__ float sex[VS_MAX_TREE];     // weight of node c's token in its parent's row
+    __shared__ float su[VS_MAX_TREE];      // u_accept
+    __shared__ int32_t sdraft[VS_MAX_TREE];
     __shared__ int32_t sremoved[VS_MAX_TREE];
+    __shared__ float sremoved_ex[VS_MAX_TREE];
     __shared__ float sred[kWalkThreads / kWave];
     __shared__ float sch[kMaxSampleChunks]; // residual weight per chunk of the current row
     __shared__ int32_t spick, slast;
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = p.T;
+    const float u_bonus = p.u_bonus[b]; // requested now, used at the very end
     const int32_t tree_code = load_tree(p.parent + (int64_t)b * T, T, sp, &sflag);
-    const int32_t* draft = p.draft + (int64_t)b * T;
+    // node tid's draft token and its logit in the parent's row (parent index clamped: a malformed
+    // tree is reported below and must not steer a load out of bounds)
+    const int32_t x_own = (tid < T) ? p.draft[(int64_t)b * T + tid] : -1;
+    const bool has_logit = tid >= 1 && tid < T && x_own >= 0 && x_own < p.V;
+    float l_own = 0.f;
+    if (has_logit) {
+        const int par = min(max(sp[tid], 0), T - 1);
+        l_own = p.logits[((int64_t)b * T + par) * p.ld + x_own];
+    }
 
-    // ---- row maxima: four threads per row merge its chunks
+    // ---- row maxima and masses: four threads per row merge its chunks, sixteen chunks per thread
+    // requested at a time (one memory round trip for vocabularies up to 64 chunks), merged online
     {
+        constexpr int kPre = 16;
         const int i = tid >> 2, sub = tid & 3;
-        float m = -INFINITY;
         const int64_t row = (int64_t)b * T + i;
-        if (i < T)
-            for (int c = sub; c < p.chunks; c += 4) m = fmaxf(m, p.part_m[row * p.chunks + c]);
-        m = fmaxf(m, __shfl_xor(m, 1));
-        m = fmaxf(m, __shfl_xor(m, 2));
-        if (i < T && sub == 0) sM[i] = m;
+        float m = -INFINITY, z = 0.f;
+        for (int c0 = sub; c0 < p.chunks; c0 += 4 * kPre) {
+            float pm[kPre], ps[kPre];
+#pragma unroll
+            for (int q = 0; q < kPre; ++q) {
+                const int c = c0 + 4 * q;
+                const bool ok = i < T && c < p.chunks;
+                pm[q] = ok ? p.part_m[row * p.chunks + c] : -INFINITY;
+                ps[q] = ok ? p.part_s[row * p.chunks + c] : 0.f;
+            }
+            float bm = m;
+#pragma unroll
+            for (int q = 0; q < kPre; ++q) bm = fmaxf(bm, pm[q]);
+            if (bm > -INFINITY) {
+                z *= __builtin_amdgcn_exp2f((m - bm) * p.k_log2); // m = -inf: z is 0 and stays 0
+#pragma unroll
+                for (int q = 0; q < kPre; ++q)
+                    if (pm[q] > -INFINITY) z += ps[q] * __builtin_amdgcn_exp2f((pm[q] - bm) * p.k_log2);
+                m = bm;
+            }
+        }
+        float mm = fmaxf(m, __shfl_xor(m, 1));
+        mm = fmaxf(mm, __shfl_xor(mm, 2));
+        if (m > -INFINITY) z *= __builtin_amdgcn_exp2f((m - mm) * p.k_log2);
+        z += __shfl_xor(z, 1);
+        z += __shfl_xor(z, 2);
+        if (i < T && sub == 0) {
+            sM[i] = mm;
+            sZ[i] = z;
+        }
+    }
+    if (tid < T) {
+        su[tid] = p.u_accept[(int64_t)b * T + tid];
+        sdraft[tid] = x_own;
     }
     __syncthreads();
     if (tree_code != VS_STATUS_OK) {
@@ -118,14 +165,11 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
         }
         return;
     }
-    // ---- every candidate's weight in its parent's row, one thread per node
+    // ---- every candidate's weight in its parent's row, one thread per node (the logit itself was
+    // requested at the top, together with the chunk statistics)
     if (tid >= 1 && tid < T) {
-        const int par = sp[tid];
-        const int32_t x = draft[tid];
-        float ex = 0.f;
-        if (x >= 0 && x < p.V && sM[par] > -INFINITY)
-            ex = __builtin_amdgcn_exp2f((p.logits[((int64_t)b * T + par) * p.ld + x] - sM[par]) * p.k_log2);
-        sex[tid] = ex;
+        const float Mp = sM[sp[tid]];
+        sex[tid] = (has_logit && Mp > -INFINITY) ? __builtin_amdgcn_exp2f((l_own - Mp) * p.k_log2) : 0.f;
     }
     __syncthreads();
 
@@ -139,7 +183,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
         __syncthreads();
         return (sred[0] + sred[1]) + (sred[2] + sred[3]);
     };
-    // This thread's 16 consecutive weights of chunk c of row `node`, removed tokens zeroed.
+    // This thread's 16 consecutive weights of chunk c of row `node`, the first nrem removed tokens zeroed.
     auto load_weights = [&](int node, int c, int nrem, float (&w)[kPerThread]) {
         const float* lg = p.logits + ((int64_t)b * T + node) * p.ld;
         const float M = sM[node];
@@ -166,66 +210,87 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
             }
         }
     };
-
-    // ---- the walk
-    int cur = 0, alen = 0, nrem = 0;
-    float Z = 0.f;
-    for (;;) {
-        // residual weights of cur's row per chunk, relative to the row maximum
-        const int64_t row = (int64_t)b * T + cur;
-        const float M = sM[cur];
-        __syncthreads(); // the previous node's sch / sremoved are no longer read
+    // Takes removed token r out of its chunk's mass (tokens 0..r are gone at that point).
+    auto remove_from_chunks = [&](int node, int r) {
+        const int xc = sremoved[r] / p.chunk_elems;
+        const float old = sch[xc];
+        float fresh = old - sremoved_ex[r];
+        if (!(fresh >= 0.25f * old)) {
+            // the subtraction cancelled most of the chunk: sum it again without the removed tokens
+            float w[kPerThread];
+            load_weights(node, xc, r + 1, w);
+            float s = 0.f;
+#pragma unroll
+            for (int e = 0; e < kPerThread; ++e) s += w[e];
+            s = wave_sum(s);
+            __syncthreads();
+            if (lane == 0) sred[wave] = s;
+            __syncthreads();
+            fresh = (sred[0] + sred[1]) + (sred[2] + sred[3]);
+        }
+        __syncthreads(); // every thread has read the old value
+        if (tid == 0) sch[xc] = fresh;
+        __syncthreads();
+    };
+    // Per-chunk masses of row `node` with the first nrem removed tokens taken out; returns their sum.
+    auto materialize = [&](int node, int nrem) -> float {
+        const int64_t row = (int64_t)b * T + node;
+        const float M = sM[node];
+        __syncthreads();
         for (int c = tid; c < p.chunks; c += kWalkThreads) {
             const float mc = p.part_m[row * p.chunks + c];
             sch[c] = (mc > -INFINITY) ? p.part_s[row * p.chunks + c] * __builtin_amdgcn_exp2f((mc - M) * p.k_log2) : 0.f;
         }
         __syncthreads();
-        Z = chunk_total();
+        for (int r = 0; r < nrem; ++r) remove_from_chunks(node, r);
+        return chunk_total();
+    };
+
+    // ---- the walk
+    int cur = 0, alen = 0, nrem = 0;
+    float Z = 0.f;
+    bool have_chunks = false;
+    for (;;) {
+        Z = sZ[cur];
         nrem = 0;
+        have_chunks = false;
         int next = -1;
         for (int c = cur + 1; c < T && next < 0; ++c) {
             if (sp[c] != cur) continue;
-            const int32_t x = draft[c];
+            const int32_t x = sdraft[c];
             bool gone = x < 0 || x >= p.V;
             for (int r = 0; r < nrem; ++r) gone = gone || sremoved[r] == x;
             const float ex = gone ? 0.f : sex[c];
             const float prob = (Z > 0.f) ? ex / Z : 0.f;
-            if (p.u_accept[(int64_t)b * T + c] < prob) {
+            if (su[c] < prob) {
                 next = c;
             } else if (!gone) {
-                const int xc = x / p.chunk_elems;
-                const float old = sch[xc];
-                __syncthreads(); // every thread has read the list and the chunk sum
-                if (tid == 0) sremoved[nrem] = x;
+                __syncthreads(); // every thread has read the list
+                if (tid == 0) {
+                    sremoved[nrem] = x;
+                    sremoved_ex[nrem] = ex;
+                }
                 ++nrem;
                 __syncthreads();
-                float fresh = old - ex;
-                if (!(fresh >= 0.25f * old)) {
-                    // the subtraction cancelled most of the chunk: sum it again without the removed tokens
-                    float w[kPerThread];
-                    load_weights(cur, xc, nrem, w);
-                    float s = 0.f;
-#pragma unroll
-                    for (int e = 0; e < kPerThread; ++e) s += w[e];
-                    s = wave_sum(s);
-                    __syncthreads();
-                    if (lane == 0) sred[wave] = s;
-                    __syncthreads();
-                    fresh = (sred[0] + sred[1]) + (sred[2] + sred[3]);
+                if (have_chunks) {
+                    remove_from_chunks(cur, nrem - 1);
+                    Z = chunk_total();
+                } else if (Z - ex >= 0.05f * Z) {
+                    Z -= ex;
+                } else {
+                    Z = materialize(cur, nrem);
+                    have_chunks = true;
                 }
-                __syncthreads();
-                if (tid == 0) sch[xc] = fresh;
-                __syncthreads();
-                Z = chunk_total();
             }
         }
         if (next < 0) break;
         cur = next;
         ++alen;
     }
+    if (!have_chunks) Z = materialize(cur, nrem);
 
     // ---- bonus token: inverse of the residual's cumulative sum, index order
-    const float target = p.u_bonus[b] * Z;
+    const float target = u_bonus * Z;
     int kb = -1;
     float before = 0.f;
     {

@@ -22,6 +22,7 @@ namespace {
 
 constexpr int kVec = 4;          // 16-byte loads per thread and chunk (chunk = 4096 floats)
 constexpr int kSelThreads = 256;
+constexpr int kExpandThreads = 1024;
 
 struct Ent {
     float v;
@@ -53,12 +54,87 @@ __device__ __forceinline__ float wave_sum(float x) {
 }
 
 constexpr int32_t kNone = INT32_MAX; // index of "no entry": loses every comparison at value -inf
+constexpr int kCandCap = 128;        // entries of a wave's candidate list in LDS
+
+// Larger float -> larger key (no NaN); every real key is > 0, which stands for "no entry".
+__device__ __forceinline__ uint32_t order_key(float v) {
+    const uint32_t u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_value(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// The first K of a wave's entries in (value descending, index ascending); every lane passes NE
+// entries (index kNone = none). emit(rank, value, index) is called once per rank 0..K-1 by
+// some lane; ranks past the number of entries get (-inf, kNone).
+// How: the K-th largest of the lanes' own maxima (found bit by bit with ballots) is a lower
+// bound of the K-th largest entry, so the entries at or above it are a small superset of the
+// answer; they are compacted into the wave's LDS list and ranked by counting. A plateau of
+// equal values or a nearly empty wave can overflow the list: then the entries are extracted
+// one by one instead. No workgroup barrier inside; cv / ci are private to the wave.
+template <int NE, typename Emit>
+__device__ __forceinline__ void wave_topk(const float (&v)[NE], const int32_t (&i)[NE], int K, float* cv,
+                                          int32_t* ci, Emit emit) {
+    const int lane = threadIdx.x & 63;
+    uint32_t best = 0;
+#pragma unroll
+    for (int e = 0; e < NE; ++e)
+        if (i[e] != kNone) best = max(best, order_key(v[e]));
+    uint32_t res = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = res | (1u << bit);
+        if (__popcll(__ballot(best >= trial)) >= K) res = trial;
+    }
+    const float tau = res ? key_value(res) : -INFINITY; // res == 0: fewer than K lanes hold entries
+    int n = 0;
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+        const bool pred = i[e] != kNone && v[e] >= tau;
+        const uint64_t mask = __ballot(pred);
+        const int pos = n + __popcll(mask & ((1ull << lane) - 1ull));
+        if (pred && pos < kCandCap) {
+            cv[pos] = v[e];
+            ci[pos] = i[e];
+        }
+        n += __popcll(mask);
+    }
+    if (n <= kCandCap) {
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); // the list is read by other lanes of this wave
+        for (int t = lane; t < n; t += kWave) {
+            const float tv = cv[t];
+            const int32_t ti = ci[t];
+            int rank = 0;
+            for (int o = 0; o < n; ++o) rank += before(cv[o], ci[o], tv, ti) ? 1 : 0;
+            if (rank < K) emit(rank, tv, ti);
+        }
+        for (int r = n + lane; r < K; r += kWave) emit(r, -INFINITY, kNone);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); // reads done before the list is reused
+    } else {
+        float last_v = INFINITY;
+        int32_t last_i = -1;
+        for (int r = 0; r < K; ++r) {
+            Ent mine = {-INFINITY, kNone};
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                if (i[e] != kNone && before(last_v, last_i, v[e], i[e]) && before(v[e], i[e], mine.v, mine.i))
+                    mine = {v[e], i[e]};
+            const Ent w = wave_first(mine);
+            if (lane == 0) emit(r, w.v, w.i);
+            last_v = w.v;
+            last_i = w.i;
+        }
+    }
+}
 
 // grid = (chunks, B*F), block = 256.
 __global__ __launch_bounds__(kArgmaxBlock) void draft_topk_partial_kernel(const DraftExpandParams p) {
     __shared__ float sv[kArgmaxBlock / kWave];
-    __shared__ int32_t si[kArgmaxBlock / kWave];
     __shared__ float ss[kArgmaxBlock / kWave];
+    __shared__ float s_cv[(kArgmaxBlock / kWave) * kCandCap];
+    __shared__ int32_t s_ci[(kArgmaxBlock / kWave) * kCandCap];
+    __shared__ float s_wv[(kArgmaxBlock / kWave) * kMaxDraftK];
+    __shared__ int32_t s_wi[(kArgmaxBlock / kWave) * kMaxDraftK];
     const int chunk = blockIdx.x;
     const int64_t row = blockIdx.y;
     const float* __restrict__ lg = p.logits + row * p.ld;
@@ -126,109 +202,123 @@ __global__ __launch_bounds__(kArgmaxBlock) void draft_topk_partial_kernel(const 
         p.part_s[row * p.chunks + chunk] = (ss[0] + ss[1]) + (ss[2] + ss[3]);
     }
 
-    // ---- the chunk's K first entries in (value descending, index ascending)
-    float last_v = INFINITY;
-    int32_t last_i = -1;
-    Ent mine = {-INFINITY, kNone}; // this thread's first entry after (last_v, last_i)
-    bool rescan = true;
-    float* out_v = p.part_tv + (row * p.chunks + chunk) * p.K;
-    int32_t* out_i = p.part_ti + (row * p.chunks + chunk) * p.K;
-    for (int r = 0; r < p.K; ++r) {
-        if (rescan) {
-            mine = {-INFINITY, kNone};
+    // ---- the chunk's K first entries in (value descending, index ascending): per wave, then merged
+    {
+        float ev[4 * kVec + 1];
+        int32_t ei[4 * kVec + 1];
 #pragma unroll
-            for (int j = 0; j < kVec; ++j)
+        for (int j = 0; j < kVec; ++j)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float v = a[4 * j + e];
-                    const int32_t i = base_idx[j] + e;
-                    if (valid(j, e) && before(last_v, last_i, v, i) && before(v, i, mine.v, mine.i)) mine = {v, i};
-                }
-            if (tail_i != kNone && before(last_v, last_i, tail_v, tail_i) && before(tail_v, tail_i, mine.v, mine.i))
-                mine = {tail_v, tail_i};
-        }
-        Ent w = wave_first(mine);
-        __syncthreads(); // sv / si are free again
-        if (lane == 0) {
-            sv[wave] = w.v;
-            si[wave] = w.i;
-        }
+            for (int e = 0; e < 4; ++e) {
+                ev[4 * j + e] = a[4 * j + e];
+                ei[4 * j + e] = valid(j, e) ? base_idx[j] + e : kNone;
+            }
+        ev[4 * kVec] = tail_v;
+        ei[4 * kVec] = tail_i;
+        const int K = p.K;
+        wave_topk(ev, ei, K, s_cv + wave * kCandCap, s_ci + wave * kCandCap, [&](int r, float v, int32_t i) {
+            s_wv[wave * kMaxDraftK + r] = v;
+            s_wi[wave * kMaxDraftK + r] = i;
+        });
         __syncthreads();
-#pragma unroll
-        for (int q = 0; q < kArgmaxBlock / kWave; ++q)
-            if (before(sv[q], si[q], w.v, w.i)) w = {sv[q], si[q]};
-        if (threadIdx.x == 0) {
-            out_v[r] = w.v;
-            out_i[r] = w.i; // kNone when the chunk has fewer than r+1 entries
+        if (wave == 0) {
+            constexpr int kWaves = kArgmaxBlock / kWave;
+            float mv[1];
+            int32_t mi[1];
+            const int w = lane / K, r = lane - w * K; // lane < kWaves * K <= 64 holds wave w's r-th entry
+            const bool has = lane < kWaves * K;
+            mv[0] = has ? s_wv[w * kMaxDraftK + r] : -INFINITY;
+            mi[0] = has ? s_wi[w * kMaxDraftK + r] : kNone;
+            float* out_v = p.part_tv + (row * p.chunks + chunk) * K;
+            int32_t* out_i = p.part_ti + (row * p.chunks + chunk) * K;
+            wave_topk(mv, mi, K, s_cv, s_ci, [&](int rr, float v, int32_t i) {
+                out_v[rr] = v;
+                out_i[rr] = i; // kNone when the chunk has fewer than rr+1 entries
+            });
         }
-        last_v = w.v;
-        last_i = w.i;
-        rescan = (mine.i == w.i); // only the winner's owner has to look for its next entry
-        if (w.i == kNone) rescan = false;
     }
 }
 
-// grid = B, block = 256.
-__global__ __launch_bounds__(kSelThreads) void draft_expand_select_kernel(const DraftExpandParams p) {
-    __shared__ float s_lse[VS_MAX_TREE];
+// grid = B, block = 1024: one wave per frontier row (rows beyond sixteen take turns).
+__global__ __launch_bounds__(kExpandThreads) void draft_expand_select_kernel(const DraftExpandParams p) {
     __shared__ float s_score[kMaxDraftCand];
     __shared__ int32_t s_token[kMaxDraftCand];
     __shared__ uint8_t s_keep[kMaxDraftCand];
+    __shared__ float s_cv[(kExpandThreads / kWave) * kCandCap];
+    __shared__ int32_t s_ci[(kExpandThreads / kWave) * kCandCap];
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int F = p.F, K = p.K, C = F * K;
     const int keep = min(K, C);
 
-    // ---- per row (one wave at a time per row): log-sum-exp and the K first entries of the merged lists
-    for (int f = wave; f < F; f += kSelThreads / kWave) {
+    // ---- per row: log-sum-exp and the K first entries of the merged chunk lists
+    for (int f = wave; f < F; f += kExpandThreads / kWave) {
         const int64_t row = (int64_t)b * F + f;
         const float* pm = p.part_m + row * p.chunks;
         const float* ps = p.part_s + row * p.chunks;
-        float m = -INFINITY;
-        for (int c = lane; c < p.chunks; c += kWave) m = fmaxf(m, pm[c]);
+        const float* tv = p.part_tv + row * p.chunks * K;
+        const int32_t* ti = p.part_ti + row * p.chunks * K;
+        const int n = p.chunks * K;
+        // everything the row needs is requested before anything is used: chunk statistics (the first
+        // 64 chunks; a longer row loops below), the chunk lists when they fit in registers, the score
+        constexpr int kRegEnt = 8;
+        const bool in_regs = n <= kWave * kRegEnt;
+        float m0 = (lane < p.chunks) ? pm[lane] : -INFINITY;
+        float s0 = (lane < p.chunks) ? ps[lane] : 0.f;
+        float rv[kRegEnt];
+        int32_t ri[kRegEnt];
+#pragma unroll
+        for (int q = 0; q < kRegEnt; ++q) {
+            const int e = lane + q * kWave;
+            rv[q] = (in_regs && e < n) ? tv[e] : -INFINITY;
+            ri[q] = (in_regs && e < n) ? ti[e] : kNone;
+        }
+        const float cum = p.cum_in ? p.cum_in[row] : 0.f;
+        float m = m0;
+        for (int c = lane + kWave; c < p.chunks; c += kWave) m = fmaxf(m, pm[c]);
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-        float z = 0.f;
-        for (int c = lane; c < p.chunks; c += kWave) {
+        float z = (m0 > -INFINITY) ? s0 * __builtin_amdgcn_exp2f((m0 - m) * 1.4426950408889634f) : 0.f;
+        for (int c = lane + kWave; c < p.chunks; c += kWave) {
             const float mc = pm[c];
             if (mc > -INFINITY) z += ps[c] * __builtin_amdgcn_exp2f((mc - m) * 1.4426950408889634f);
         }
         z = wave_sum(z);
         const float lse = m + __logf(z);
-        if (lane == 0) s_lse[f] = lse;
-        const float* tv = p.part_tv + row * p.chunks * K;
-        const int32_t* ti = p.part_ti + row * p.chunks * K;
-        const int n = p.chunks * K;
-        float last_v = INFINITY;
-        int32_t last_i = -1;
-        const float cum = p.cum_in ? p.cum_in[row] : 0.f;
-        for (int r = 0; r < K; ++r) {
-            Ent mine = {-INFINITY, kNone};
-            for (int q = lane; q < n; q += kWave) {
-                const float v = tv[q];
-                const int32_t i = ti[q];
-                if (i != kNone && before(last_v, last_i, v, i) && before(v, i, mine.v, mine.i)) mine = {v, i};
+        auto emit = [&](int r, float v, int32_t i) {
+            s_token[f * K + r] = i;
+            s_score[f * K + r] = cum + (v - lse);
+        };
+        if (in_regs) {
+            wave_topk(rv, ri, K, s_cv + wave * kCandCap, s_ci + wave * kCandCap, emit);
+        } else { // very long rows: the lists are re-read from the workspace (L2) for every extracted entry
+            float last_v = INFINITY;
+            int32_t last_i = -1;
+            for (int r = 0; r < K; ++r) {
+                Ent mine = {-INFINITY, kNone};
+                for (int q = lane; q < n; q += kWave) {
+                    const float v = tv[q];
+                    const int32_t i = ti[q];
+                    if (i != kNone && before(last_v, last_i, v, i) && before(v, i, mine.v, mine.i)) mine = {v, i};
+                }
+                const Ent w = wave_first(mine);
+                if (lane == 0) emit(r, w.v, w.i);
+                last_v = w.v;
+                last_i = w.i;
             }
-            const Ent w = wave_first(mine);
-            if (lane == 0) {
-                s_token[f * K + r] = w.i;
-                s_score[f * K + r] = cum + (w.v - lse);
-            }
-            last_v = w.v;
-            last_i = w.i;
         }
     }
     __syncthreads();
 
     // ---- next frontier: the `keep` first candidates in (score descending, index ascending), by counting
-    for (int c = tid; c < C; c += kSelThreads) {
+    for (int c = tid; c < C; c += kExpandThreads) {
         const float sc = s_score[c];
         int rank = 0;
         for (int o = 0; o < C; ++o) rank += before(s_score[o], o, sc, c) ? 1 : 0;
         s_keep[c] = rank < keep ? 1 : 0;
     }
     __syncthreads();
-    for (int c = tid; c < C; c += kSelThreads) {
+    for (int c = tid; c < C; c += kExpandThreads) {
         const int64_t g = (int64_t)b * p.cand_capacity + p.cand_base + c;
         p.cand_token[g] = s_token[c];
         p.cand_score[g] = s_score[c];
@@ -315,7 +405,7 @@ hipError_t launch_draft_expand(const DraftExpandParams& p, hipStream_t s) {
     hipLaunchKernelGGL(draft_topk_partial_kernel, dim3(p.chunks, p.B * p.F), dim3(kArgmaxBlock), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(draft_expand_select_kernel, dim3(p.B), dim3(kSelThreads), 0, s, p);
+    hipLaunchKernelGGL(draft_expand_select_kernel, dim3(p.B), dim3(kExpandThreads), 0, s, p);
     return hipGetLastError();
 }
 
