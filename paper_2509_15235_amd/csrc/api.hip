@@ -141,14 +141,16 @@ Plan make_plan(const vs_attn_desc* d) {
     pl.row_groups = (need + pl.waves - 1) / pl.waves;
     const int units = units0 * pl.row_groups;
     if (splits <= 0) {
-        // large: fill the CUs once. Small launches are latency-bound: workgroup dispatch
-        // (about 30 ns each) and the combine grow with the split count, the loop with the
-        // keys per split; measured optima were 4 iterations of 64 keys per split for short
-        // sequences and 8 for long ones, with at most ~1.5 workgroups per CU.
+        // large: fill the CUs once. Small launches are latency-bound: the write-back of the
+        // partial results at the end of the kernel (about 0.2 us per split for a C3-sized
+        // launch) and the combine grow with the split count, the loop (about 2 us per 64 keys
+        // with one wave per SIMD) with the keys per split; measured optima were 3 iterations
+        // of 64 keys per split for short sequences and 8 for long ones, with at most ~1.5
+        // workgroups per CU.
         if (big) {
             splits = 256 / units;
         } else {
-            const int iters = tiles <= 32 ? 4 : (tiles <= 64 ? 5 : 8);
+            const int iters = tiles <= 32 ? 3 : (tiles <= 64 ? 5 : 8);
             splits = (tiles + iters - 1) / iters;
             const int cap = (384 + units / 2) / units;
             if (splits > cap) splits = cap;
@@ -169,7 +171,7 @@ Plan make_plan(const vs_attn_desc* d) {
 size_t workspace_bytes(const vs_attn_desc* d, const Plan& pl) {
     if (pl.impl != VS_IMPL_MFMA || pl.num_splits <= 1) return 0;
     const size_t prow = (size_t)d->B * d->Hkv * pl.num_splits * pl.rows_pad;
-    return align_up(prow * d->d * sizeof(float)) + align_up(prow * 2 * sizeof(float));
+    return align_up(prow * d->d * sizeof(uint16_t)) + align_up(prow * 2 * sizeof(float));
 }
 
 constexpr int kArgmaxChunk = 4096; // floats per workgroup of the scan: 256 threads x 4 x 16 bytes
@@ -298,8 +300,8 @@ int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const 
     p.total_wgs = pl.total_wgs;
     if (need > 0) {
         const size_t prow = (size_t)desc->B * desc->Hkv * pl.num_splits * pl.rows_pad;
-        p.part_o = (float*)workspace;
-        p.part_ml = (float*)((char*)workspace + align_up(prow * desc->d * sizeof(float)));
+        p.part_o = (uint16_t*)workspace;
+        p.part_ml = (float*)((char*)workspace + align_up(prow * desc->d * sizeof(uint16_t)));
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;

@@ -22,10 +22,10 @@
 //   the row-major V tile on its way out of LDS), B = P (registers: the C layout of S^T
 //   is, after rounding to bf16, already a B operand; the V reads pick keys in that order)
 //
-// With one split the normalised result is written as bf16; otherwise unnormalised
-// partials (O, running max, running sum) go to the workspace, laid out exactly as the
-// accumulator registers are (so every store is a contiguous 1 KB per wave), and the
-// combine kernel merges them.
+// With one split the normalised result is written as bf16; otherwise partials (O divided
+// by the row's sum, as fp16; running max and sum as fp32) go to the workspace, laid out
+// exactly as the accumulator registers are (so every store is contiguous per wave), and
+// the combine kernel merges them.
 #include <type_traits>
 
 #include "attn_mfma_common.h"
@@ -454,15 +454,14 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
         } else {
             if (row_base + rb * kRowBlock >= p.rows) continue; // whole block is padding
             const int64_t blk = part_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
-            float* po = p.part_o + blk * (kRowBlock * D) + lane * 4;
+            uint16_t* po = p.part_o + blk * (kRowBlock * D) + lane * 4;
+            const float inv = l > 0.f ? 1.f / l : 0.f; // no visible key in this split: zeros, weight 0
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const f32x4 w = {acc[rb][db][4 * q4], acc[rb][db][4 * q4 + 1], acc[rb][db][4 * q4 + 2],
-                                     acc[rb][db][4 * q4 + 3]};
-                    *(f32x4*)(po + (db * 4 + q4) * 256) = w;
-                }
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *(u32x2*)(po + (db * 4 + q4) * 256) = pack_partial(acc[rb][db][4 * q4], acc[rb][db][4 * q4 + 1],
+                                                                      acc[rb][db][4 * q4 + 2], acc[rb][db][4 * q4 + 3], inv);
             if (half == 0) {
                 const f32x2 ml = {m2[rb], l};
                 const int64_t mlb = ml_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
@@ -472,7 +471,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     }
 }
 
-// Merges the key splits: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s per query row.
+// Merges the key splits: out = sum_s w_s (O_s / l_s) / sum_s w_s with w_s = 2^(m_s - M) l_s per query row
+// (the main kernels store O_s / l_s, see pack_partial).
 // One wave per (sequence, KV head, 32-row block, 32-channel block); lanes map to the
 // partials exactly as the accumulator registers did, the result is transposed through LDS
 // so that the bf16 rows leave as 16-byte stores. The kernel is pure latency, so the prefix
@@ -493,7 +493,7 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
     const f32x2* gml = (const f32x2*)p.part_ml + ml_block(p, unit, 0, rbk) + col; // + s * kRowBlock
     const int64_t blk0 = part_block(p, unit, 0, rbk);
     const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
-    const float* po0 = p.part_o + blk0 * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
+    const uint16_t* po0 = p.part_o + blk0 * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
 
     float den = 0.f, M = -INFINITY;
     f32x4 num[4];
@@ -502,16 +502,16 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
     int nsplit = 0;
     for (int s0 = 0; s0 < p.num_splits; s0 += kCombineBatch) {
         f32x2 ml[kCombineBatch];
-        f32x4 o[kCombineBatch][4];
+        u32x2 o[kCombineBatch][4];
 #pragma unroll
         for (int u = 0; u < kCombineBatch; ++u)
             if (s0 + u < p.num_splits) ml[u] = __builtin_nontemporal_load(gml + (s0 + u) * kRowBlock);
 #pragma unroll
         for (int u = 0; u < kCombineBatch; ++u)
             if (s0 + u < p.num_splits) {
-                const float* po = po0 + (s0 + u) * blk_stride * (kRowBlock * D);
+                const uint16_t* po = po0 + (s0 + u) * blk_stride * (kRowBlock * D);
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) o[u][q4] = __builtin_nontemporal_load((const f32x4*)(po + q4 * 256));
+                for (int q4 = 0; q4 < 4; ++q4) o[u][q4] = __builtin_nontemporal_load((const u32x2*)(po + q4 * 256));
             }
         if (s0 == 0) {
             if (!prefix_ok(p, S)) return;
@@ -531,10 +531,11 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
         for (int u = 0; u < kCombineBatch; ++u)
             if (s0 + u < nsplit) { // uniform
                 // a split that saw no visible key for the row has max -inf, sum 0 and zero partials
-                const float w = (ml[u][0] != -INFINITY) ? __builtin_amdgcn_exp2f(ml[u][0] - M) : 0.f;
-                den += w * ml[u][1];
+                // the split's row is stored normalised: its weight is 2^(m_s - M) * l_s
+                const float w = (ml[u][0] != -INFINITY) ? __builtin_amdgcn_exp2f(ml[u][0] - M) * ml[u][1] : 0.f;
+                den += w;
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * o[u][q4];
+                for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * unpack_partial(o[u][q4]);
             }
     }
     const float inv = 1.f / den;

@@ -26,7 +26,7 @@ struct AttnParams {
     const uint64_t* tree_mask;  // may be null
     const int32_t* block_table; // paged only
     int32_t* status;            // may be null
-    float* part_o;              // [unit][split][rows_pad][d] unnormalised partial outputs
+    uint16_t* part_o;           // [unit][split][rows_pad][d] partial outputs, each row normalised by its own sum, fp16
     float* part_ml;             // [unit][split][rows_pad][2] running max (log2 domain), sum
     int32_t B, T, Hq, Hkv, d, group;
     int32_t rows;               // T * group: query rows per (sequence, KV head)
