@@ -68,6 +68,10 @@ def _load():
         lib.oracle_draft_tree_build.argtypes = [i32p, f32p, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                 i32p, i32p, i32p, i32p]
         lib.oracle_draft_tree_build.restype = ctypes.c_int
+        lib.oracle_compress_attention.argtypes = [
+            f32p, f32p, f32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+            ctypes.c_double, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int32, ctypes.c_int64, f64p]
+        lib.oracle_compress_attention.restype = ctypes.c_int
         lib.oracle_kv_commit.argtypes = [
             ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
             i32p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, ctypes.c_int32,
@@ -304,3 +308,29 @@ def draft_tree_build_seq(cand_token, cand_score, cand_parent, N, root_token=-1):
                                          _p(node_cand, ctypes.c_int32), ctypes.byref(T))
     t = int(T.value) if rc == OK else 0
     return int(rc), parent[:t], tokens[:t], node_cand[:t]
+
+
+def compress_attention_seq(q, k_cache, v_cache, r, scale, Hkv, *, block_table=None, block_size=16):
+    """Vision-adaptor compression attention for one image: q f32 [nq, Hq, d] (the learnable
+    queries), K / V f32 [Hkv, cap, d] (contiguous) or [n_blocks, Hkv, block_size, d] (paged), of
+    which the first r logical tokens are the image embeddings. Returns float64 [nq, Hq, d]."""
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    k_cache = np.ascontiguousarray(k_cache, dtype=np.float32)
+    v_cache = np.ascontiguousarray(v_cache, dtype=np.float32)
+    nq, Hq, d = q.shape
+    out = np.zeros((nq, Hq, d), dtype=np.float64)
+    if block_table is None:
+        cap = k_cache.shape[1]
+        assert k_cache.shape[0] == Hkv and r <= cap
+        paged, sh, st, sb = 0, cap * d, d, 0
+        bt = np.zeros(1, dtype=np.int32)
+    else:
+        bt = _i32(block_table)
+        assert k_cache.shape[1] == Hkv and k_cache.shape[2] == block_size
+        paged, sh, st, sb = 1, block_size * d, d, Hkv * block_size * d
+    rc = _load().oracle_compress_attention(_p(q, ctypes.c_float), _p(k_cache, ctypes.c_float),
+                                           _p(v_cache, ctypes.c_float), nq, Hq, Hkv, d, int(r), float(scale), paged,
+                                           sh, st, _p(bt, ctypes.c_int32), block_size, sb, _p(out, ctypes.c_double))
+    if rc != OK:
+        raise ValueError(f"oracle_compress_attention failed with code {rc}")
+    return out

@@ -38,6 +38,9 @@
  *   oracle_draft_tree_build  exhaustive search over ancestor-closed subsets on tiny
  *       candidate sets (the selection maximises total probability), K = 1 gives a chain,
  *       structural invariants, a hand-worked example.
+ *   oracle_compress_attention  an independent fp64 softmax-attention routine, the paper's
+ *       closed form for R identical keys plus one unique key (Eq. 3-4), hand-worked
+ *       weights, zero keys = mean over exactly r values, untouched slots beyond r.
  *   oracle_kv_commit  an out-of-place gather from a pristine copy of the cache
  *       (numpy fancy indexing), identity on a chain path, untouched bytes
  *       outside the destination rows, and the closed loop: attention over the
@@ -532,4 +535,51 @@ int oracle_draft_tree_build(const int32_t* cand_token, const float* cand_score, 
     free(picked);
     free(node_of);
     return rc;
+}
+
+/* Compression attention of the vision adaptor (Section 3.2 "a lightweight vision adaptor":
+ * a fixed set of learnable query vectors attends to the image's visual features, which serve
+ * as keys and values; every query sees every image embedding; Eq. 1 with a softmax scale).
+ * The projections and the rest of the adaptor's encoder layer are outside this path: q, K, V
+ * arrive already projected.
+ *
+ *   s_j = scale * <q[i,h,:], K[kv,j,:]>,  j = 0 .. r-1,  kv = h / (Hq / Hkv)
+ *   out[i,h,:] = sum_j exp(s_j - max s) V[kv,j,:] / sum_j exp(s_j - max s)      (ascending j)
+ *
+ * q [nq][Hq][d] float, out [nq][Hq][d] double; K / V addressed like the tree attention's
+ * caches (contiguous or paged); r >= 1 keys; slots beyond r are never read. */
+int oracle_compress_attention(const float* q, const float* k_cache, const float* v_cache, int32_t nq,
+                              int32_t Hq, int32_t Hkv, int32_t d, int32_t r, double scale, int32_t paged,
+                              int64_t stride_head, int64_t stride_tok, const int32_t* block_table,
+                              int32_t block_size, int64_t stride_block, double* out) {
+    if (nq < 1 || Hkv < 1 || Hq % Hkv != 0 || d < 1 || r < 1) return ORACLE_BAD_SIZE;
+    oracle_kv_layout L = {paged, stride_head, stride_tok, block_table, block_size, stride_block};
+    const int32_t group = Hq / Hkv;
+    double* s = (double*)malloc(sizeof(double) * (size_t)r);
+    if (!s) return ORACLE_BAD_SIZE;
+    for (int32_t i = 0; i < nq; ++i)
+        for (int32_t h = 0; h < Hq; ++h) {
+            const int32_t kv = h / group;
+            const float* qv = q + ((int64_t)i * Hq + h) * d;
+            double m = -INFINITY;
+            for (int32_t j = 0; j < r; ++j) {
+                const float* kj = k_cache + token_offset(&L, kv, j);
+                double dot = 0.0;
+                for (int32_t c = 0; c < d; ++c) dot += (double)qv[c] * (double)kj[c];
+                s[j] = scale * dot;
+                if (s[j] > m) m = s[j];
+            }
+            double* o = out + ((int64_t)i * Hq + h) * d;
+            for (int32_t c = 0; c < d; ++c) o[c] = 0.0;
+            double denom = 0.0;
+            for (int32_t j = 0; j < r; ++j) {
+                const double w = exp(s[j] - m);
+                const float* vj = v_cache + token_offset(&L, kv, j);
+                denom += w;
+                for (int32_t c = 0; c < d; ++c) o[c] += w * (double)vj[c];
+            }
+            for (int32_t c = 0; c < d; ++c) o[c] /= denom;
+        }
+    free(s);
+    return ORACLE_OK;
 }
