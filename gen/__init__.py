@@ -412,3 +412,30 @@ def draft_logits(seed: int, b: int, level: int, F: int, V: int, sharp: float = 3
     trained draft head's logits do."""
     g = rng(seed, STREAM_DRAFT, b * 64 + level)
     return (sharp * g.standard_normal((F, V), dtype=np.float32)).astype(np.float32)
+
+
+STREAM_ADAPTOR = 14
+
+
+def compress_inputs(seed: int, B: int, nq: int, Hq: int, Hkv: int, d: int, lens, dtype: str = "bf16",
+                    cap: Optional[int] = None):
+    """Inputs of the vision adaptor's compression attention: nq query vectors per image (stand-ins
+    for the learnable queries after their projection), K / V of lens[b] image embeddings per image
+    in a contiguous [B, Hkv, cap, d] cache whose slots beyond lens[b] are NaN. Values N(0,1),
+    rounded once to the storage dtype. Returns a dict of f32 values (and bf16 bits when dtype is
+    bf16)."""
+    lens = np.asarray(lens, dtype=np.int32)
+    cap = int(lens.max()) + 5 if cap is None else cap
+    g = rng(seed, STREAM_ADAPTOR)
+    q = g.standard_normal((B, nq, Hq, d), dtype=np.float32)
+    k = g.standard_normal((B, Hkv, cap, d), dtype=np.float32)
+    v = g.standard_normal((B, Hkv, cap, d), dtype=np.float32)
+    qv, qb = _store(q, dtype)
+    kv, kb = _store(k, dtype)
+    vv, vb = _store(v, dtype)
+    for b in range(B):
+        for arr, bits in ((kv, kb), (vv, vb)):
+            arr[b, :, lens[b]:] = np.nan
+            if bits is not None:
+                bits[b, :, lens[b]:] = 0x7FC0
+    return dict(q=qv, k=kv, v=vv, q_bits=qb, k_bits=kb, v_bits=vb, lens=lens, cap=cap, scale=1.0 / np.sqrt(d))

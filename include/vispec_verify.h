@@ -17,6 +17,8 @@
  *   vs_draft_expand /         builds the draft tree that the next step verifies: top-K
  *   vs_draft_tree_build       expansion scored by cumulative log-probability, best-N selection
  *                             (Section 3.1's dynamic draft tree, Appendix A's parameters)
+ *   vs_compress_attention     the vision adaptor's attention: a few learnable queries over the
+ *                             image embeddings (Section 3.2)
  *   vs_tree_kv_commit         keeps the accepted path's K/V rows, in order, behind the
  *                             prefix of the pre-allocated cache (Section 3.1, Appendix A)
  *
@@ -186,6 +188,28 @@ int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const 
                                  const int32_t* tree_parent, const uint64_t* tree_mask, void* out,
                                  int32_t* status, void* workspace, size_t workspace_bytes,
                                  void* stream);
+
+/*
+ * Compression attention of the vision adaptor (Section 3.2: a fixed set of learnable query
+ * vectors attends to the image's visual features, which serve as keys and values, condensing
+ * them into a few compressed image tokens; Eq. 1 with the softmax scale). Every query sees
+ * every image embedding and nothing else. The adaptor's projections and the rest of its
+ * encoder layer are outside this library: q, k, v arrive projected.
+ * The descriptor is read as for vs_tree_verify_attention with these meanings: T = number of
+ * learnable queries (1..64; the paper studies 1 to 64), max_prefix_len = the largest kv_len
+ * (>= 1), k / v = the image embeddings' keys and values in either cache layout.
+ *   q        [B,T,Hq,d]  in  (a caller with one shared query set passes B copies)
+ *   kv_len   [B] int32   in, number of image embeddings of each image, 1 <= kv_len <= max_prefix_len;
+ *            anything else is reported as VS_STATUS_BAD_PREFIX
+ *   out      [B,T,Hq,d]  out, the compressed image tokens before the output projection
+ *   status, workspace (vs_compress_attention_workspace_bytes), stream: as above
+ * Runs the same kernels as the verification call (no tree slots, no mask).
+ */
+size_t vs_compress_attention_workspace_bytes(const vs_attn_desc* desc);     /* 0 on invalid desc */
+
+int32_t vs_compress_attention(const vs_attn_desc* desc, const void* q, const void* k, const void* v,
+                              const int32_t* kv_len, void* out, int32_t* status, void* workspace,
+                              size_t workspace_bytes, void* stream);
 
 size_t vs_accept_workspace_bytes(int32_t B, int32_t T, int32_t V);
 

@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     vs_version, vs_strerror, vs_status_string, vs_tree_validate_host, vs_tree_mask_build,
     vs_attention_plan, vs_attention_workspace_bytes, vs_tree_verify_attention,
     vs_accept_workspace_bytes, vs_tree_accept, vs_accept_sample_workspace_bytes, vs_tree_accept_sample,
+    vs_compress_attention_workspace_bytes, vs_compress_attention,
     vs_draft_expand_workspace_bytes, vs_draft_expand, vs_draft_tree_build, vs_tree_kv_commit, EXPORTED_SYMBOLS,
 )

@@ -16,6 +16,7 @@ EXPORTED_SYMBOLS = [
     "vs_attention_plan", "vs_attention_workspace_bytes", "vs_tree_verify_attention",
     "vs_accept_workspace_bytes", "vs_tree_accept", "vs_accept_sample_workspace_bytes", "vs_tree_accept_sample",
     "vs_draft_expand_workspace_bytes", "vs_draft_expand", "vs_draft_tree_build", "vs_tree_kv_commit",
+    "vs_compress_attention_workspace_bytes", "vs_compress_attention",
 ]
 
 
@@ -90,6 +91,10 @@ def lib():
         L.vs_attention_workspace_bytes.restype = sz
         L.vs_tree_verify_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vs_tree_verify_attention.restype = i32
+        L.vs_compress_attention_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc)]
+        L.vs_compress_attention_workspace_bytes.restype = sz
+        L.vs_compress_attention.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_compress_attention.restype = i32
         L.vs_accept_workspace_bytes.argtypes = [i32, i32, i32]
         L.vs_accept_workspace_bytes.restype = sz
         L.vs_tree_accept.argtypes = [vp, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -160,6 +165,16 @@ def vs_tree_verify_attention(desc: AttnDesc, q, k_cache, v_cache, prefix_len, tr
     return lib().vs_tree_verify_attention(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                           _ptr(prefix_len), _ptr(tree_parent), _ptr(tree_mask), _ptr(out),
                                           _ptr(status), _ptr(workspace), workspace_bytes, _ptr(stream))
+
+
+def vs_compress_attention_workspace_bytes(desc: AttnDesc) -> int:
+    return lib().vs_compress_attention_workspace_bytes(ctypes.byref(desc))
+
+
+def vs_compress_attention(desc: AttnDesc, q, k, v, kv_len, out, status=None, workspace=None, workspace_bytes=0,
+                          stream=None) -> int:
+    return lib().vs_compress_attention(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(kv_len), _ptr(out),
+                                       _ptr(status), _ptr(workspace), workspace_bytes, _ptr(stream))
 
 
 def vs_accept_workspace_bytes(B: int, T: int, V: int) -> int:

@@ -19,7 +19,7 @@ struct Plan {
 };
 
 // Shape / dtype / layout checks that need no device. Returns VS_OK or a vs_error.
-int32_t check_desc(const vs_attn_desc* d) {
+int32_t check_desc(const vs_attn_desc* d, int tree = 1) {
     if (!d) return VS_ERR_NULL;
     if (d->B < 1 || d->T < 1 || d->T > VS_MAX_TREE || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0)
         return VS_ERR_SHAPE;
@@ -41,7 +41,8 @@ int32_t check_desc(const vs_attn_desc* d) {
         if (d->waves_per_group != 0 && d->waves_per_group != 4 && d->waves_per_group != 8) return VS_ERR_SHAPE;
     }
     if (d->stride_head < 0 || d->stride_tok < d->d) return VS_ERR_LAYOUT;
-    const int64_t need = (int64_t)d->max_prefix_len + d->T;
+    const int64_t need = (int64_t)d->max_prefix_len + (tree ? d->T : 0);
+    if (!tree && d->max_prefix_len < 1) return VS_ERR_SHAPE;
     if (d->paged) {
         if (!is_pow2(d->block_size) || d->block_size < 16) return VS_ERR_LAYOUT;
         if (d->max_blocks < 1 || d->num_blocks < 1 || d->stride_block < 0) return VS_ERR_LAYOUT;
@@ -63,7 +64,7 @@ int32_t check_desc(const vs_attn_desc* d) {
     return VS_OK;
 }
 
-Plan make_plan(const vs_attn_desc* d) {
+Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     Plan pl{};
     const int group = d->Hq / d->Hkv;
     pl.rows = d->T * group;
@@ -79,7 +80,7 @@ Plan make_plan(const vs_attn_desc* d) {
         return pl;
     }
     const int nrb = pl.rows_pad / kRowBlock;
-    const int tiles = ((int64_t)d->max_prefix_len + d->T + kIterKeys - 1) / kIterKeys;
+    const int tiles = ((int64_t)d->max_prefix_len + (tree ? d->T : 0) + kIterKeys - 1) / kIterKeys;
     const int units0 = d->B * d->Hkv;
     // Launch shape, from measurements on MI355X (C2..C5-shaped inputs):
     //  * few units (one layer of one sequence): latency-bound; straight-loop kernel, one
@@ -247,14 +248,15 @@ size_t vs_attention_workspace_bytes(const vs_attn_desc* desc) {
     return workspace_bytes(desc, make_plan(desc));
 }
 
-int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const void* k_cache,
-                                 const void* v_cache, const int32_t* prefix_len, const int32_t* tree_parent,
-                                 const uint64_t* tree_mask, void* out, int32_t* status, void* workspace,
-                                 size_t workspace_bytes_given, void* stream) {
-    if (!desc || !q || !k_cache || !v_cache || !prefix_len || !tree_parent || !out) return VS_ERR_NULL;
-    const int32_t rc = check_desc(desc);
+namespace {
+// Shared by the two attention entry points. tree = 1: the T queries are tree nodes whose own
+// K/V sit behind the prefix; tree = 0: T learnable queries over the prefix alone.
+int32_t enqueue_attention(const vs_attn_desc* desc, int tree, const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* prefix_len, const int32_t* tree_parent, const uint64_t* tree_mask, void* out,
+                          int32_t* status, void* workspace, size_t workspace_bytes_given, void* stream) {
+    const int32_t rc = check_desc(desc, tree);
     if (rc != VS_OK) return rc;
-    const Plan pl = make_plan(desc);
+    const Plan pl = make_plan(desc, tree);
     if (pl.impl == VS_IMPL_MFMA && !(aligned16(q) && aligned16(k_cache) && aligned16(v_cache) && aligned16(out)))
         return VS_ERR_LAYOUT;
     const size_t need = workspace_bytes(desc, pl);
@@ -273,6 +275,7 @@ int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const 
     p.status = status;
     p.B = desc->B;
     p.T = desc->T;
+    p.tree_keys = tree ? desc->T : 0;
     p.Hq = desc->Hq;
     p.Hkv = desc->Hkv;
     p.d = desc->d;
@@ -313,6 +316,29 @@ int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const 
         if (e == hipSuccess && pl.num_splits > 1) e = launch_attention_combine(p, desc->dtype, s);
     }
     return e == hipSuccess ? VS_OK : VS_ERR_HIP;
+}
+} // namespace
+
+int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const void* k_cache,
+                                 const void* v_cache, const int32_t* prefix_len, const int32_t* tree_parent,
+                                 const uint64_t* tree_mask, void* out, int32_t* status, void* workspace,
+                                 size_t workspace_bytes_given, void* stream) {
+    if (!desc || !q || !k_cache || !v_cache || !prefix_len || !tree_parent || !out) return VS_ERR_NULL;
+    return enqueue_attention(desc, 1, q, k_cache, v_cache, prefix_len, tree_parent, tree_mask, out, status, workspace,
+                             workspace_bytes_given, stream);
+}
+
+size_t vs_compress_attention_workspace_bytes(const vs_attn_desc* desc) {
+    if (check_desc(desc, 0) != VS_OK) return 0;
+    return workspace_bytes(desc, make_plan(desc, 0));
+}
+
+int32_t vs_compress_attention(const vs_attn_desc* desc, const void* q, const void* k, const void* v,
+                              const int32_t* kv_len, void* out, int32_t* status, void* workspace,
+                              size_t workspace_bytes_given, void* stream) {
+    if (!desc || !q || !k || !v || !kv_len || !out) return VS_ERR_NULL;
+    return enqueue_attention(desc, 0, q, k, v, kv_len, nullptr, nullptr, out, status, workspace, workspace_bytes_given,
+                             stream);
 }
 
 size_t vs_accept_workspace_bytes(int32_t B, int32_t T, int32_t V) {

@@ -40,20 +40,26 @@ __global__ __launch_bounds__(kWave) void attn_generic_kernel(const AttnParams p)
     const int lane = threadIdx.x;
     const int kvh = h / p.group;
 
-    const int32_t tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
+    int32_t tree_code = VS_STATUS_OK;
+    if (p.tree_keys == 0) {
+        if (lane == 0) sflag = 0;
+        __syncthreads();
+    } else {
+        tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
+    }
     const int32_t S = p.prefix_len[b];
     const bool s_ok = prefix_ok(p, S);
     if (node == 0 && h == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
     if (tree_code != VS_STATUS_OK || !s_ok) return;
 
-    const uint64_t mask = p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node);
+    const uint64_t mask = p.tree_keys == 0 ? 0ull : (p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node));
     const TIn* q = (const TIn*)p.q + (((int64_t)b * p.T + node) * p.Hq + h) * D;
     for (int c = lane; c < D; c += kWave) sq[c] = Elem<TIn>::load(q + c);
     __syncthreads();
 
     const TIn* kbase = (const TIn*)p.k;
     const TIn* vbase = (const TIn*)p.v;
-    const int n = S + p.T;
+    const int n = S + p.tree_keys;
     float m = -INFINITY, l = 0.f;
     float acc[CPL];
 #pragma unroll

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     // masks of a malformed tree); otherwise check it here.
     const int32_t S = p.prefix_len[b]; // requested before the tree is read: one latency, not two
     int32_t tree_code = VS_STATUS_OK;
-    if (p.tree_mask) {
+    if (p.tree_mask || p.tree_keys == 0) {
         if (tid == 0) sflag = 0;
         __syncthreads();
     } else {
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
     if (tree_code != VS_STATUS_OK || !s_ok) return;
 
-    const int nk = S + p.T;
+    const int nk = S + p.tree_keys;
     const int k0 = split * p.keys_per_split;
     if (k0 >= nk) return;
     const int k1 = min(nk, k0 + p.keys_per_split);
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
         const int r = min(row_base + rb * kRowBlock + col, p.rows - 1);
         const int node = r / p.group;
         const int hq = kvh * p.group + (r - node * p.group);
-        mask[rb] = p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node);
+        mask[rb] = p.tree_keys == 0 ? 0ull : (p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node));
         const uint16_t* qr = qbase + (((int64_t)b * p.T + node) * p.Hq + hq) * D + half * 8;
         if (wave_active) {
 #pragma unroll
@@ -515,7 +515,7 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
             }
         if (s0 == 0) {
             if (!prefix_ok(p, S)) return;
-            nsplit = min(p.num_splits, (S + p.T + p.keys_per_split - 1) / p.keys_per_split);
+            nsplit = min(p.num_splits, (S + p.tree_keys + p.keys_per_split - 1) / p.keys_per_split);
         }
         // this batch's maximum joins the running one; what was summed so far is rescaled
         float Mb = M;

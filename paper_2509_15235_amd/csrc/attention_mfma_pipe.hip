@@ -68,7 +68,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
 
     const int32_t S = p.prefix_len[b]; // requested before the tree is read: one latency, not two
     int32_t tree_code = VS_STATUS_OK;
-    if (p.tree_mask) {
+    if (p.tree_mask || p.tree_keys == 0) {
         if (tid == 0) sflag = 0;
         __syncthreads();
     } else {
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
     if (tree_code != VS_STATUS_OK || !s_ok) return;
 
-    const int nk = S + p.T;
+    const int nk = S + p.tree_keys;
     const int k0 = split * p.keys_per_split;
     if (k0 >= nk) return;
     const int k1 = min(nk, k0 + p.keys_per_split);
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
         const int r = min(row_base + rb * kRowBlock + col, p.rows - 1);
         const int node = r / p.group;
         const int hq = kvh * p.group + (r - node * p.group);
-        mask[rb] = p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node);
+        mask[rb] = p.tree_keys == 0 ? 0ull : (p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node));
         const uint16_t* qr = qbase + (((int64_t)b * p.T + node) * p.Hq + hq) * D + half * 8;
         if (wave_active) {
 #pragma unroll

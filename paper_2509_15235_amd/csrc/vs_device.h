@@ -64,7 +64,8 @@ __device__ __forceinline__ uint64_t ancestor_mask(const int32_t* sp, int node) {
 // Is this sequence's prefix length usable? (inside the host's bound and inside the cache)
 __device__ __forceinline__ bool prefix_ok(const AttnParams& p, int32_t S) {
     if (S < 0 || S > p.max_prefix_len) return false;
-    const int64_t need = (int64_t)S + p.T;
+    if (p.tree_keys == 0 && S < 1) return false; // nothing to attend to
+    const int64_t need = (int64_t)S + p.tree_keys;
     const int64_t have = p.paged ? (int64_t)p.max_blocks * p.block_size : p.capacity;
     return need <= have;
 }
@@ -91,7 +92,7 @@ __device__ __forceinline__ void report_status(const AttnParams& p, int b, int32_
     if (code == VS_STATUS_OK && !s_ok) code = VS_STATUS_BAD_PREFIX;
     if (code == VS_STATUS_OK && p.paged) {
         // *sflag is 0 here (load_tree leaves it 0 for a valid tree)
-        const int nblk = (S + p.T + p.block_size - 1) >> p.block_shift;
+        const int nblk = (S + p.tree_keys + p.block_size - 1) >> p.block_shift;
         for (int i = threadIdx.x; i < nblk; i += blockDim.x) {
             const int32_t blk = p.block_table[(int64_t)b * p.max_blocks + i];
             if ((uint32_t)blk >= (uint32_t)p.num_blocks) atomicOr(sflag, 4);

@@ -29,6 +29,8 @@ struct AttnParams {
     uint16_t* part_o;           // [unit][split][rows_pad][d] partial outputs, each row normalised by its own sum, fp16
     float* part_ml;             // [unit][split][rows_pad][2] running max (log2 domain), sum
     int32_t B, T, Hq, Hkv, d, group;
+    int32_t tree_keys;          // T when the queries' own K/V sit behind the prefix (verification), 0 when they
+                                // attend to the prefix alone (the vision adaptor's compression attention)
     int32_t rows;               // T * group: query rows per (sequence, KV head)
     int32_t rows_pad;           // rows rounded up to a multiple of kRowBlock
     int32_t max_prefix_len;

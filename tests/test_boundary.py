@@ -195,6 +195,21 @@ def test_draft_calls_reject_bad_arguments_before_any_launch():
     assert bd(N=0) == -2 and bd(N=64) == -2 and bd(B=0) == -2
 
 
+def test_compress_attention_rejects_bad_arguments_before_any_launch():
+    g = 4096  # never dereferenced
+    d = _desc(T=16)
+    assert vs.vs_compress_attention(d, None, g, g, g, g) == -1
+    assert vs.vs_compress_attention(d, g, g, g, None, g) == -1
+    assert vs.vs_compress_attention(_desc(T=65), g, g, g, g, g) == -2
+    assert vs.vs_compress_attention(_desc(T=16, max_prefix_len=0), g, g, g, g, g) == -2       # no image embeddings at all
+    assert vs.vs_compress_attention(d, g + 2, g, g, g, g) == -6                              # misaligned q
+    assert vs.vs_compress_attention(_desc(T=16, num_splits=4), g, g, g, g, g, None, None, 0) == -4
+    # the queries' own K/V are not in the cache: a cache of exactly max_prefix_len tokens is enough
+    tight = _desc(T=16, max_prefix_len=1800)
+    assert vs.vs_compress_attention_workspace_bytes(tight) > 0 and vs.vs_attention_workspace_bytes(tight) == 0
+    assert vs.vs_compress_attention_workspace_bytes(_desc(T=0)) == 0
+
+
 def test_kv_commit_rejects_bad_arguments_before_any_launch():
     def kd(**kw):
         d = vs.KVDesc(B=2, T=8, Hkv=2, d=64, dtype=vs.VS_BF16, num_layers=3, stride_layer=2 * 2 * 100 * 64,
