@@ -200,6 +200,20 @@ def main():
         check(vs.vs_draft_tree_build(d_tok, d_score, d_par, 1, dcap, dcap, DN, None, d_parent, d_tokens, d_cand, d_num,
                                      status, stream))
 
+    # the vision adaptor's compression attention on the same buffers: T query vectors over the image's
+    # embeddings (C3: 1296 image tokens), one image, one (adaptor) layer
+    n_img = min(1296, S)
+    desc_c = vs.AttnDesc(B=1, T=T, Hq=Hq, Hkv=Hkv, d=d, dtype=vs.VS_BF16, softmax_scale=float(scale),
+                         max_prefix_len=n_img, paged=0, capacity=cap, stride_seq=Hkv * cap * d, stride_head=cap * d,
+                         stride_tok=d)
+    len_c = torch.full((1,), n_img, device=dev, dtype=torch.int32)
+    cws_bytes = vs.vs_compress_attention_workspace_bytes(desc_c)
+    cws = torch.empty(max(cws_bytes, 256), device=dev, dtype=torch.uint8)
+    out_c = torch.empty((1, T, Hq, d), device=dev, dtype=torch.bfloat16)
+
+    def enqueue_compress(st, stream):
+        check(vs.vs_compress_attention(desc_c, st["q"], st["k"], st["v"], len_c, out_c, status, cws, cws_bytes, stream))
+
     stream = torch.cuda.Stream(device=dev)
     sp = stream.cuda_stream
     check(vs.vs_tree_mask_build(parentL, L, T, maskL, depth, status, sp))
@@ -244,9 +258,15 @@ def main():
                     and (d_parent.cpu().numpy()[0] == o_par).all() and (d_tokens.cpu().numpy()[0] == o_tok).all()
                     and (d_tok.cpu().numpy()[0, :DK] == e_tok).all()
                     and np.abs(d_score.cpu().numpy()[0, :DK] - e_sc).max() <= 3e-5)
-    if not (err0 <= 2e-2 and accept_ok and commit_ok and sample_ok and draft_ok):
+    with torch.cuda.stream(stream):
+        enqueue_compress(sets[0], sp)
+    stream.synchronize()
+    ref_c = oracle.compress_attention_seq(host_layers[0].q[0], host_layers[0].k_cache[0], host_layers[0].v_cache[0],
+                                          n_img, scale, Hkv)
+    err_c = float(np.abs(out_c[0].float().cpu().numpy() - ref_c).max())
+    if not (err0 <= 2e-2 and accept_ok and commit_ok and sample_ok and draft_ok and err_c <= 2e-2):
         print(f"bench.py: parity check failed (attention max|err| {err0}, accept ok {accept_ok}, commit ok {commit_ok}, "
-              f"sample ok {sample_ok}, draft ok {draft_ok})", file=sys.stderr)
+              f"sample ok {sample_ok}, draft ok {draft_ok}, compression attention max|err| {err_c})", file=sys.stderr)
         sys.exit(4)
 
     # ---------------------------------------------------------------- runners (HIP graphs or eager)
@@ -302,6 +322,7 @@ def main():
     ms_sample = per_call(enqueue_sample, max(args.steps // 2, 25), max(args.warmup, 5))
     ms_draft = per_call(enqueue_draft, max(args.steps // 2, 25), max(args.warmup, 5))
     ms_commit = per_call(enqueue_commit, max(args.steps // 2, 25), max(args.warmup, 5))
+    ms_compress = per_call(enqueue_compress, max(args.steps // 2, 25), max(args.warmup, 5))
 
     # a plain device copy of known size: the reference that scales rocprofv3's FETCH_SIZE /
     # WRITE_SIZE counters when HBM traffic of the kernels above is derived from a --pmc run
@@ -366,6 +387,9 @@ def main():
              "note": f"{DD} x vs_draft_expand (K={DK}) + vs_draft_tree_build (N={DN}) = 7 dependent kernels over "
                      f"{draft_rows} logits rows; the draft model between the expansions is not included"}
 
+    compress = {"bound": "latency", "us_per_launch": round(ms_compress * 1e3, 2), "queries": T, "image_embeddings": n_img,
+                "note": "vs_compress_attention (vision adaptor): one image, one layer; not part of the step"}
+
     commit_bytes = 2 * 2 * L * Hkv * int(o_alen[0]) * d * eb                               # rows read + rows written, K and V
     commit = {"bound": "latency", "us_per_launch": round(ms_commit * 1e3, 2), "accepted_len": int(o_alen[0]),
               "bytes": commit_bytes, "note": "after the step (not part of it): moves accepted rows of all layers"}
@@ -390,9 +414,10 @@ def main():
         "config": {"workload": f"{cfg.name}: B=1 Hq={Hq} Hkv={Hkv} d={d} prefix={S} tree={T} nodes depth<={cfg.max_depth} "
                                f"layers={L} vocab={V}; step = mask_build + {L} x attention + accept",
                    "hip_graph": not args.no_graph, "buffer_sets": nsets},
-        "roofline": roofline, "per_layer_call": per_layer, "argmax": argmax, "accept_sample": sample, "draft_tree": draft, "kv_commit": commit, "cpu_baseline": cpu,
+        "roofline": roofline, "per_layer_call": per_layer, "argmax": argmax, "accept_sample": sample, "draft_tree": draft, "compress_attention": compress, "kv_commit": commit, "cpu_baseline": cpu,
         "parity": {"attention_max_abs_err_layer0": err0, "accept_bit_exact": accept_ok, "commit_bit_exact": commit_ok,
-                   "sample_outcome_valid": sample_ok, "draft_tree_bit_exact": draft_ok},
+                   "sample_outcome_valid": sample_ok, "draft_tree_bit_exact": draft_ok,
+                   "compress_attention_max_abs_err": err_c},
     }
     print(json.dumps(line))
 
