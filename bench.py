@@ -312,7 +312,11 @@ def main():
         ms, _ = timed(build_runner(enqueue_all), iters, warmup)
         return ms / nsets
 
-    ms_folded = per_call(enqueue_folded, max(args.steps // 4, 12), 3)
+    # The folded launch is the one heavy kernel here, and the GPU needs about 100 ms of sustained
+    # heavy work before its clocks settle (idle sclk 157 MHz; the same kernel measures 70 - 75 us
+    # per launch over the first few milliseconds and 62 us from ~150 ms on): warm up for >= 150 ms,
+    # then time >= 100 ms of back-to-back launches.
+    ms_folded = per_call(enqueue_folded, max(args.steps // 4, 320), 480)
 
     def enqueue_one_layer(st, stream_):
         check(vs.vs_tree_verify_attention(desc1, st["q"], st["k"], st["v"], prefix1, parent1, mask, st["out"],

@@ -325,9 +325,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // slots ahead, and one share of the softmax of S(cur) -> P(cur) for row block rb. The
     // softmax is cut into 16 groups per row block: 4 of running-maximum work (the last one
     // fixes the reference), 8 of two exponentials each, 4 of bf16 packing.
-    auto fast_step = [&](f32x16(&s_next)[RPW], const uint16_t* kslot, const uint16_t* vslot,
-                         const bf16x8(&p_prev)[RPW][2], f32x16(&s_cur)[RPW], bf16x8(&p_cur)[RPW][2],
-                         float(&alpha)[RPW]) __attribute__((always_inline)) {
+    // copy_tag >= 0 (a register set): the step also carries the iteration's tile copies, one
+    // tile per four slots - the staged tile goes to LDS and its registers are refilled with the
+    // tile two groups ahead - so that the LDS writes trickle in between the fragment reads
+    // instead of arriving as one 32 KB burst that stalls every wave's reads behind it.
+    auto fast_step = [&](auto copy_tag, auto lfast_tag, int g, f32x16(&s_next)[RPW], const uint16_t* kslot,
+                         const uint16_t* vslot, const bf16x8(&p_prev)[RPW][2], f32x16(&s_cur)[RPW],
+                         bf16x8(&p_cur)[RPW][2], float(&alpha)[RPW]) __attribute__((always_inline)) {
+        constexpr int CSET = decltype(copy_tag)::value;
         constexpr int NF = KS + 2 * DB; // fragments = MFMA slots per row block
         constexpr int GPS = 16 / NF;    // softmax groups per slot
         static_assert(16 % NF == 0, "softmax groups must divide evenly over the slots");
@@ -351,7 +356,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
                 frag[f % (PF + 1)] = __builtin_bit_cast(u32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
         };
-        float mx[RPW], nm[RPW], psum[RPW];
+        float mx[RPW], nm[RPW], psum[RPW], psum2[RPW];
         u32x4 pw[RPW][2];
         auto softmax_group = [&](int rb, int g) __attribute__((always_inline)) {
             f32x16& sc = s_cur[rb];
@@ -365,21 +370,34 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
                     m2[rb] = m_new;
                     nm[rb] = -m_new;
                     psum[rb] = 0.f;
+                    psum2[rb] = 0.f;
                 }
             } else if (g < 12) {
 #pragma unroll
-                for (int e = 2 * (g - 4); e < 2 * (g - 4) + 2; ++e) {
+                for (int e = 2 * (g - 4); e < 2 * (g - 4) + 2; ++e)
                     sc[e] = __builtin_amdgcn_exp2f(fmaf(sc[e], p.scale_log2, nm[rb]));
-                    psum[rb] += sc[e];
+                // the previous group's pair joins the sum here, one group late, so that the add
+                // never waits for an exponential; two running sums keep the adds independent. The
+                // empty asm keeps each add in its slot (otherwise all sixteen are sunk behind the
+                // step as one dependent chain, out of the MFMAs' shadow).
+                if (g > 4) {
+                    psum[rb] += sc[2 * (g - 5)];
+                    psum2[rb] += sc[2 * (g - 5) + 1];
+                    asm volatile("" : "+v"(psum[rb]), "+v"(psum2[rb]));
                 }
             } else {
                 const int q = g - 12, sl = q >> 1;
+                if (g == 12) {
+                    psum[rb] += sc[14];
+                    psum2[rb] += sc[15];
+                }
 #pragma unroll
                 for (int e = 2 * (q & 1); e < 2 * (q & 1) + 2; ++e) {
                     const f32x2 pr = {sc[8 * sl + 2 * e], sc[8 * sl + 2 * e + 1]};
                     pw[rb][sl][e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+                    asm volatile("" : "+v"(pw[rb][sl][e]));
                 }
-                if (g == 15) lsum[rb] = lsum[rb] * alpha[rb] + psum[rb];
+                if (g == 15) lsum[rb] = lsum[rb] * alpha[rb] + (psum[rb] + psum2[rb]);
             }
         };
 #pragma unroll
@@ -402,7 +420,26 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
                     acc[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_prev[rb][sl], acc[rb][db], 0, 0, 0);
                 }
 #pragma unroll
-                for (int g = f * GPS; g < (f + 1) * GPS; ++g) softmax_group(rb, g);
+                for (int sg = f * GPS; sg < (f + 1) * GPS; ++sg) softmax_group(rb, sg);
+                if constexpr (CSET >= 0) {
+                    if (rb == 0 && f % (NF / 4) == 1) {
+                        constexpr int SETC = CSET >= 0 ? CSET : 0;
+                        const int part = f / (NF / 4); // 0, 1: K(2g+3), K(2g+4); 2, 3: V(2g+1), V(2g+2)
+                        if (part == 0) {
+                            stash_tile(std::false_type{}, sK[(2 * g + 3) & 3], stage[SETC][0]);
+                            load_tile(lfast_tag, std::false_type{}, 2 * (g + 2) + 3, stage[SETC][0]);
+                        } else if (part == 1) {
+                            stash_tile(std::false_type{}, sK[(2 * g + 4) & 3], stage[SETC][1]);
+                            load_tile(lfast_tag, std::false_type{}, 2 * (g + 2) + 4, stage[SETC][1]);
+                        } else if (part == 2) {
+                            stash_tile(std::true_type{}, sV[(2 * g + 1) & 3], stage[SETC][2]);
+                            load_tile(lfast_tag, std::true_type{}, 2 * (g + 2) + 1, stage[SETC][2]);
+                        } else {
+                            stash_tile(std::true_type{}, sV[(2 * g + 2) & 3], stage[SETC][3]);
+                            load_tile(lfast_tag, std::true_type{}, 2 * (g + 2) + 2, stage[SETC][3]);
+                        }
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -451,7 +488,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
             float alpha[RPW];
             if constexpr (FAST) {
                 // the very first step applies all-zero probabilities to V(0)
-                fast_step(sb, sK[tb & 3], sV[ta ? (ta - 1) & 3 : 0], pb, sa, pa, alpha);
+                fast_step(std::integral_constant<int, -1>{}, lfast_tag, g, sb, sK[tb & 3], sV[ta ? (ta - 1) & 3 : 0], pb, sa,
+                          pa, alpha);
             } else {
                 if (tb < n) qk(sb, sK[tb & 3]);
                 if (ta > 0) pv(sV[(ta - 1) & 3], pb);
@@ -462,13 +500,20 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
         // In the middle of the iteration: group g (requested one and a half iterations ago) goes
         // to LDS and its registers are refilled with group g + 2. The LDS writes complete under
         // the second tile's work; the barrier at the end publishes them for iteration g + 1.
-        stash_group(set_tag, g);
-        load_group(lfast_tag, set_tag, g + 2);
+        // (the fast form spreads the same copies over the slots of its second step, see fast_step;
+        // waves without rows have no such step and copy here)
+        // (with four waves a tile is two blocks per wave and the interleaved form runs out of registers)
+        constexpr bool SPREAD = FAST && BPW == 1;
+        if (!SPREAD || !wave_active) {
+            stash_group(set_tag, g);
+            load_group(lfast_tag, set_tag, g + 2);
+        }
         // second tile: S(ta + 2), O(ta) | P(tb)
         if (wave_active) {
             float alpha[RPW];
             if constexpr (FAST) {
-                fast_step(sa, sK[(ta + 2) & 3], sV[ta & 3], pa, sb, pb, alpha);
+                using copy_t = std::conditional_t<SPREAD, decltype(set_tag), std::integral_constant<int, -1>>;
+                fast_step(copy_t{}, lfast_tag, g, sa, sK[(ta + 2) & 3], sV[ta & 3], pa, sb, pb, alpha);
                 rescale(alpha);
             } else {
                 if (ta + 2 < n) qk(sa, sK[(ta + 2) & 3]);
