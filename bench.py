@@ -364,7 +364,8 @@ def main():
     except OSError:
         pass
     def kernel_name(pl):
-        k = "attn_mfma_pipe_kernel" if pl.schedule == vs.VS_SCHED_PIPELINED else "attn_mfma_kernel"
+        k = {vs.VS_SCHED_PIPELINED: "attn_mfma_pipe_kernel", vs.VS_SCHED_RESIDENT: "attn_mfma_resident_kernel"}.get(
+            pl.schedule, "attn_mfma_kernel")
         return k + (" + attn_combine_kernel" if pl.combine else "")
 
     roofline.update({"kernel": kernel_name(planL), "launch": f"{L} layers folded as batch entries",

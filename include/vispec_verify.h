@@ -80,10 +80,18 @@ typedef enum vs_dtype { VS_BF16 = 0, VS_F32 = 1 } vs_dtype;
 /* Which attention kernel to run. AUTO picks MFMA for bf16 and GENERIC for fp32. */
 typedef enum vs_attn_impl { VS_IMPL_AUTO = 0, VS_IMPL_GENERIC = 1, VS_IMPL_MFMA = 2 } vs_attn_impl;
 
-/* How the MFMA kernel orders a tile's three stages (scores, softmax, output update):
- * LOOP runs them back to back; PIPELINED overlaps the matrix-core work of the
- * neighbouring tiles with the current tile's softmax. Same results up to fp32 rounding. */
-typedef enum vs_attn_schedule { VS_SCHED_AUTO = 0, VS_SCHED_LOOP = 1, VS_SCHED_PIPELINED = 2 } vs_attn_schedule;
+/* How the MFMA kernels are scheduled. LOOP streams 64-key tiles through LDS and runs a tile's
+ * three stages (scores, softmax, output update) back to back; PIPELINED overlaps the matrix-core
+ * work of the neighbouring tiles with the current tile's softmax (launches with many units);
+ * RESIDENT copies a split's whole key range (at most 256 keys) into LDS first and splits the
+ * keys once more among the waves of a workgroup (latency-bound launches with few units).
+ * Same results up to fp32 rounding. AUTO chooses from the shape. */
+typedef enum vs_attn_schedule {
+    VS_SCHED_AUTO = 0,
+    VS_SCHED_LOOP = 1,
+    VS_SCHED_PIPELINED = 2,
+    VS_SCHED_RESIDENT = 3
+} vs_attn_schedule;
 
 int32_t vs_version(void);
 const char* vs_strerror(int32_t err);       /* static string for a vs_error */

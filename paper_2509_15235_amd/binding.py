@@ -9,7 +9,7 @@ _LIB_PATH = os.path.join(_HERE, "libvispec_verify.so")
 
 VS_BF16, VS_F32 = 0, 1
 VS_IMPL_AUTO, VS_IMPL_GENERIC, VS_IMPL_MFMA = 0, 1, 2
-VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED = 0, 1, 2
+VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED, VS_SCHED_RESIDENT = 0, 1, 2, 3
 
 EXPORTED_SYMBOLS = [
     "vs_version", "vs_strerror", "vs_status_string", "vs_tree_validate_host", "vs_tree_mask_build",

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvispec_verify.so")
-SOURCES = ["api.hip", "tree_mask.hip", "attention_generic.hip", "attention_mfma.hip", "attention_mfma_pipe.hip", "accept.hip", "accept_sample.hip", "draft_tree.hip",
+SOURCES = ["api.hip", "tree_mask.hip", "attention_generic.hip", "attention_mfma.hip", "attention_mfma_pipe.hip", "attention_mfma_resident.hip", "accept.hip", "accept_sample.hip", "draft_tree.hip",
            "kv_commit.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -16,6 +16,7 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 struct Plan {
     int32_t impl, rpw, waves, row_groups, rows, rows_pad, num_splits, keys_per_split, total_wgs, schedule;
+    int32_t res_rb; // resident schedule: row blocks per workgroup (4, 2 or 1)
 };
 
 // Shape / dtype / layout checks that need no device. Returns VS_OK or a vs_error.
@@ -33,8 +34,11 @@ int32_t check_desc(const vs_attn_desc* d, int tree = 1) {
     if (d->waves_per_group != 0 && d->waves_per_group != 1 && d->waves_per_group != 2 && d->waves_per_group != 4 &&
         d->waves_per_group != 8)
         return VS_ERR_SHAPE;
-    if (d->schedule != VS_SCHED_AUTO && d->schedule != VS_SCHED_LOOP && d->schedule != VS_SCHED_PIPELINED)
+    if (d->schedule != VS_SCHED_AUTO && d->schedule != VS_SCHED_LOOP && d->schedule != VS_SCHED_PIPELINED &&
+        d->schedule != VS_SCHED_RESIDENT)
         return VS_ERR_SHAPE;
+    if (d->schedule == VS_SCHED_RESIDENT && (d->rows_per_wave == 2 || (d->waves_per_group != 0 && d->waves_per_group != 8)))
+        return VS_ERR_SHAPE; // eight waves, one row block each
     if (d->schedule == VS_SCHED_PIPELINED) {
         // the pipelined kernel exists for one row block per wave and four or eight waves
         if (d->rows_per_wave == 2) return VS_ERR_SHAPE;
@@ -95,7 +99,35 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     const bool big = units0 >= 48;
     int rpw = d->rows_per_wave, waves = d->waves_per_group, splits = d->num_splits;
     const bool pipe_ok = (rpw == 0 || rpw == 1) && (waves == 0 || waves == 4 || waves == 8);
-    pl.schedule = d->schedule == VS_SCHED_AUTO ? (big && pipe_ok ? VS_SCHED_PIPELINED : VS_SCHED_LOOP) : d->schedule;
+    // few units, several row blocks, a short sequence (at most 2048 keys) and no caller's
+    // choice that it cannot honour: the LDS-resident
+    // kernel, whose second split of the keys among the waves shortens each workgroup's loop
+    // (measured on a C3-sized layer: 12.1 + 5.1 us with 7 splits against 13.9 + 5.7 us with 10
+    // for the streaming loop; slower than the loop for two row blocks and for 5000+ keys,
+    // where its 256-key limit forces too many partial results)
+    const bool resident_ok = !big && nrb >= 3 && tiles <= 32 && (rpw == 0 || rpw == 1) && (waves == 0 || waves == 8) &&
+                             (splits <= 0 || (tiles + splits - 1) / splits <= kResidentMaxKeys / kIterKeys);
+    pl.schedule = d->schedule != VS_SCHED_AUTO ? d->schedule
+                  : big && pipe_ok             ? VS_SCHED_PIPELINED
+                  : resident_ok                ? VS_SCHED_RESIDENT
+                                               : VS_SCHED_LOOP;
+    if (pl.schedule == VS_SCHED_RESIDENT) {
+        // eight waves = res_rb row blocks x 8 / res_rb key parts; a split holds at most
+        // kResidentMaxKeys keys (four 64-key tiles)
+        pl.rpw = 1;
+        pl.waves = 8;
+        pl.res_rb = nrb >= 3 ? 4 : nrb;
+        pl.row_groups = (nrb + pl.res_rb - 1) / pl.res_rb;
+        const int max_tiles = kResidentMaxKeys / kIterKeys;
+        if (splits <= 0) splits = (tiles + max_tiles - 1) / max_tiles; // full splits: fewest partial results (measured)
+        int tps = (tiles + splits - 1) / splits;
+        if (tps > max_tiles) tps = max_tiles;
+        if (tps < 1) tps = 1;
+        pl.keys_per_split = tps * kIterKeys;
+        pl.num_splits = (tiles + tps - 1) / tps;
+        pl.total_wgs = units0 * pl.row_groups * pl.num_splits;
+        return pl;
+    }
     if (pl.schedule == VS_SCHED_PIPELINED) {
         rpw = 1;
         if (!waves) waves = nrb > 4 ? 8 : 4;
@@ -312,7 +344,8 @@ int32_t enqueue_attention(const vs_attn_desc* desc, int tree, const void* q, con
         e = launch_attention_generic(p, desc->dtype, s);
     } else {
         e = pl.schedule == VS_SCHED_PIPELINED ? launch_attention_mfma_pipe(p, pl.rpw, pl.waves, s)
-                                              : launch_attention_mfma(p, pl.rpw, pl.waves, s);
+            : pl.schedule == VS_SCHED_RESIDENT ? launch_attention_mfma_resident(p, pl.res_rb, s)
+                                               : launch_attention_mfma(p, pl.rpw, pl.waves, s);
         if (e == hipSuccess && pl.num_splits > 1) e = launch_attention_combine(p, desc->dtype, s);
     }
     return e == hipSuccess ? VS_OK : VS_ERR_HIP;

@@ -1,0 +1,341 @@
+// Tree-masked attention for small launches (one layer of one sequence): the whole key range
+// of a split is resident in LDS and the keys are split once more inside the workgroup.
+//
+// Math and MFMA layouts are those of attention_mfma.hip (paper Eq. 1 with a softmax scale over
+// the prefix plus the ancestor-or-self tree slots, Section 3.1): S^T = K . Q^T with
+// v_mfma_f32_32x32x16_bf16, a lane holds 16 keys of ONE query row, the probabilities are the
+// B operand of O^T += V^T . P^T, V is transposed by ds_read_b64_tr_b16 on its way out of LDS.
+//
+// Why another schedule. A launch with few (sequence, KV head) units is latency-bound: with one
+// wave per SIMD the streaming kernel spends 2 us per 64-key iteration of which the matrix cores
+// work 0.4 us - the rest is a single wave issuing its tile copy, LDS writes, barrier and
+// softmax one dependent instruction after the other. Here a workgroup of eight waves owns
+// NRB row blocks x KQ = 8 / NRB key parts: all waves first copy the split's keys and values
+// (at most 256 keys, 128 KB) into LDS with every load in flight at once, then each wave runs
+// its key part for its row block with no further copies or barriers (two waves per SIMD cover
+// each other's stalls), and the key parts are merged through LDS (log-sum-exp, like the
+// combine kernel does for the splits). Split partials and final rows leave as in the
+// streaming kernels, so the combine kernel and the workspace layout are shared.
+#include <type_traits>
+
+#include "attn_mfma_common.h"
+
+namespace vs {
+
+namespace {
+
+constexpr int kResWaves = 8;
+constexpr int kResMaxTiles = kResidentMaxKeys / kTileKeys; // 32-key tiles of one split
+
+template <int D, int NRB>
+__global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(const AttnParams p) {
+    constexpr int KS = D / 16;          // k-steps of the S^T product
+    constexpr int DB = D / 32;          // 32-channel blocks of the output
+    constexpr int KQ = kResWaves / NRB; // key parts inside the workgroup
+    constexpr int SUB = kTileKeys * D;  // elements per 32-key tile of K (or V)
+    constexpr int BPS = SUB * 2 / 1024; // 1 KB copy blocks per tile
+    constexpr int LPR = D / 8;          // lanes (16-byte chunks) per row
+    constexpr int RPI = 64 / LPR;       // rows per load instruction
+    constexpr int TPW = kResMaxTiles * BPS / kResWaves; // copy blocks per wave and tensor
+    static_assert(kResMaxTiles * BPS % kResWaves == 0, "copy blocks divide over the waves");
+    constexpr int MERGE_FLOATS = 64 * (DB * 16 + 2); // what a wave hands to the merge: accumulators, max, sum
+    static_assert((KQ - 1) * NRB * MERGE_FLOATS * 4 <= 2 * kResMaxTiles * SUB * 2, "merge area fits in the tile area");
+
+    // tiles: K[t] at smem + t*SUB, V[t] at smem + (kResMaxTiles + t)*SUB; after the last tile has
+    // been consumed the same memory carries the key parts' results to the merging waves
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * kResMaxTiles * SUB];
+    __shared__ int32_t sp[VS_MAX_TREE];
+    __shared__ int32_t sflag;
+    uint16_t* sK = smem;
+    uint16_t* sV = smem + kResMaxTiles * SUB;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5;
+    const int col = lane & 31;
+    const int rbw = wave % NRB; // row block inside the group
+    const int kq = wave / NRB;  // key part
+
+    // workgroup id -> (sequence, KV head, split, row group); same XCD-aware remap as the other kernels
+    const int per_xcd = (p.total_wgs + 7) >> 3;
+    const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (v >= p.total_wgs) return;
+    const int rg = v % p.row_groups;
+    int rest = v / p.row_groups;
+    const int split = rest % p.num_splits;
+    rest /= p.num_splits;
+    const int kvh = rest % p.Hkv;
+    const int b = rest / p.Hkv;
+
+    const int32_t S = p.prefix_len[b]; // requested first, needed last: everything below is issued before it arrives
+
+    // ---- copy the split's keys and values: copy block i = tile i / BPS, rows RPI * (i % BPS) ..;
+    // wave w takes blocks w, w + 8, ...; one load instruction reads RPI whole rows (1 KB of
+    // consecutive memory). The loads do not wait for the prefix length: they are clamped to
+    // the cache (not to the sequence), and rows that turn out to lie past the sequence's last
+    // key are zeroed on their way into LDS (whatever the cache holds there - NaN included -
+    // must not meet a zero probability in the V product). A block-table entry outside the pool
+    // reads block 0. Chunk c of tile row r lands where the fragment reads expect it (same
+    // placement as the streaming kernel):
+    //   K: ((r/16)*DB + c/4) * 1024 + (c%4) * 256 + ((r%16) ^ 4*(c%4)) * 16
+    //   V: ((r/16)*DB + c/4) * 1024 + (4*(r%16) + c%4) * 16
+    // (No branch around a block's loads or stores: a conditional assignment of the staging
+    // array makes the compiler spill the whole array at every branch. Slots of tiles past the
+    // split's last one receive zeros and are never read.)
+    const uint16_t* kbase = (const uint16_t*)p.k;
+    const uint16_t* vbase = (const uint16_t*)p.v;
+    const int64_t head_base = (p.paged ? 0 : (int64_t)b * p.stride_seq) + (int64_t)kvh * p.stride_head;
+    const int stride_tok = (int)p.stride_tok;
+    const int lrow = lane / LPR, lchunk = lane % LPR;
+    const int k0 = split * p.keys_per_split; // the host keeps k0 below max_prefix_len + tree_keys, hence inside the cache
+    const int64_t cache_tokens = p.paged ? (int64_t)p.max_blocks * p.block_size : p.capacity;
+    const int kend = (int)(cache_tokens < (int64_t)k0 + p.keys_per_split ? cache_tokens : (int64_t)k0 + p.keys_per_split);
+    u32x4 kreg[TPW], vreg[TPW];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) {
+        const int i = wave + kResWaves * j; // copy block, uniform per wave
+        const int r0 = min(k0 + kTileKeys * (i / BPS) + RPI * (i % BPS), kend - 1); // RPI divides 16: one cache block in paged mode
+        int tok = min(r0 + lrow, kend - 1);
+        int64_t base = head_base;
+        if (p.paged) {
+            int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (r0 >> p.block_shift)];
+            if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
+            base += (int64_t)blk * p.stride_block;
+            tok &= p.block_size - 1;
+        }
+        const uint32_t off = (uint32_t)(tok * stride_tok + lchunk * 8);
+        kreg[j] = *(const u32x4*)(kbase + base + off);
+        vreg[j] = *(const u32x4*)(vbase + base + off);
+    }
+
+    // ---- this wave's rows, mask and queries (in flight together with the tiles)
+    const int row_base = rg * (NRB * kRowBlock) + rbw * kRowBlock;
+    const bool wave_active = row_base < p.rows;
+    const int r = min(row_base + col, p.rows - 1); // rows past the end repeat the last row (results discarded)
+    const int node = r / p.group;
+    const int hq = kvh * p.group + (r - node * p.group);
+    bf16x8 qf[KS];
+    {
+        const uint16_t* qr = (const uint16_t*)p.q + (((int64_t)b * p.T + node) * p.Hq + hq) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qr + ks * 16));
+    }
+
+    int32_t tree_code = VS_STATUS_OK;
+    if (p.tree_mask || p.tree_keys == 0) {
+        if (tid == 0) sflag = 0;
+        __syncthreads();
+    } else {
+        tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
+    }
+    const uint64_t mask = p.tree_keys == 0 ? 0ull : (p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : (tree_code == VS_STATUS_OK ? ancestor_mask(sp, node) : 0ull));
+    const bool s_ok = prefix_ok(p, S);
+    if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
+    if (tree_code != VS_STATUS_OK || !s_ok) return;
+
+    const int nk = S + p.tree_keys;
+    if (k0 >= nk) return;
+    const int k1 = min(nk, k0 + p.keys_per_split);
+    const int nt = (k1 - k0 + kTileKeys - 1) / kTileKeys; // tiles of this split, <= kResMaxTiles
+
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) {
+        const int i = wave + kResWaves * j; // < kResMaxTiles * BPS: always inside the tile area
+        const int t = i / BPS, rr = (i % BPS) * RPI + lrow, c = lchunk;
+        const bool live = k0 + kTileKeys * t + rr < k1;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        const uint32_t ko = (uint32_t)(((rr >> 4) * DB + (c >> 2)) * 1024 + (c & 3) * 256 + (((rr & 15) ^ (4 * (c & 3))) * 16));
+        const uint32_t vo = (uint32_t)(((rr >> 4) * DB + (c >> 2)) * 1024 + (4 * (rr & 15) + (c & 3)) * 16);
+        *(u32x4*)((char*)(sK + t * SUB) + ko) = live ? kreg[j] : zero;
+        *(u32x4*)((char*)(sV + t * SUB) + vo) = live ? vreg[j] : zero;
+    }
+    __syncthreads();
+
+    // ---- this wave's key part: tiles [t_begin, t_end)
+    const int per_part = (nt + KQ - 1) / KQ;
+    const int t_begin = min(nt, kq * per_part), t_end = min(nt, t_begin + per_part);
+
+    float m2 = -INFINITY, lsum = 0.f; // running reference (log2 domain, scaled) and this lane's share of the sum
+    f32x16 acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[db][q] = 0.f;
+
+    // per-lane LDS offsets (elements); everything else is a compile-time immediate
+    const int k_lane[2] = {(col >> 4) * (DB * 512) + half * 128 + ((col & 15) ^ (4 * half)) * 8,
+                           (col >> 4) * (DB * 512) + half * 128 + ((col & 15) ^ (8 + 4 * half)) * 8};
+    const int t16 = lane & 15;
+    const int v_lane = half * 128 + (t16 >> 2) * 32 + ((lane >> 4) & 1) * 16 + ((t16 >> 1) & 1) * 8 + (t16 & 1) * 4;
+
+    auto tile = [&](auto masked_tag, int t) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const uint16_t* kt_ = sK + t * SUB;
+        const uint16_t* vt_ = sV + t * SUB + v_lane;
+        // S^T = K . Q^T: lane (col, half) gets keys 8*(q/4) + 4*half + q%4 of row `col`
+        f32x16 s;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) s[q] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)(kt_ + k_lane[ks & 1] + ks * 256));
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s, 0, 0, 0);
+        }
+        if constexpr (MASKED) {
+            const int rel = k0 + t * kTileKeys + 4 * half - S; // tree slot of this lane's key 0 (negative: prefix)
+            const uint32_t tree_end = (uint32_t)(k1 - S);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int sh = rel + 8 * (q >> 2) + (q & 3);
+                const uint32_t bit = (uint32_t)(mask >> (sh & 63)) & 1u;
+                const bool vis = (sh < 0) | (((uint32_t)sh < tree_end) & (bit != 0));
+                s[q] = vis ? s[q] : -INFINITY;
+            }
+        }
+        float mx = max3(s[0], s[1], s[2]);
+#pragma unroll
+        for (int q = 3; q < 15; q += 2) mx = max3(mx, s[q], s[q + 1]);
+        mx = fmaxf(mx, s[15]);
+        mx = half_max(mx);
+        // lazy reference: moves only when the tile's maximum exceeds it by more than kLazy
+        const float mt = mx * p.scale_log2;
+        const float m_new = (mt > m2 + kLazy) ? mt : m2;
+        const float m_use = (MASKED && m_new == -INFINITY) ? 0.f : m_new; // no visible key yet
+        const float alpha = __builtin_amdgcn_exp2f(m2 - m_use);
+        m2 = m_new;
+        float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 16; q += 2) {
+            s[q] = __builtin_amdgcn_exp2f(fmaf(s[q], p.scale_log2, -m_use)); // exp2(-inf) = 0
+            s[q + 1] = __builtin_amdgcn_exp2f(fmaf(s[q + 1], p.scale_log2, -m_use));
+            ps0 += s[q];
+            ps1 += s[q + 1];
+        }
+        lsum = lsum * alpha + (ps0 + ps1);
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[db][q] *= alpha;
+        }
+        bf16x8 pf[2];
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            u32x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const f32x2 pr = {s[8 * sl + 2 * e], s[8 * sl + 2 * e + 1]};
+                w[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+            }
+            pf[sl] = __builtin_bit_cast(bf16x8, w);
+        }
+        // O^T += V^T . P^T: the A operand comes from two transposing reads of 4 keys x 16 channels
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vt_ + sl * (DB * 512) + db * 512));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vt_ + sl * (DB * 512) + db * 512 + 256));
+                const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[sl], acc[db], 0, 0, 0);
+            }
+    };
+    if (wave_active) {
+        // tiles that end at or before min(S, k1) hold prefix keys only
+        const int n_plain = max(0, min(S, k1) - k0) / kTileKeys;
+        int t = t_begin;
+        const int t_plain = min(t_end, n_plain);
+#pragma clang loop unroll(disable)
+        for (; t < t_plain; ++t) tile(std::false_type{}, t);
+#pragma clang loop unroll(disable)
+        for (; t < t_end; ++t) tile(std::true_type{}, t);
+    }
+
+    // ---- merge the key parts: parts 1.. hand (accumulators, reference, sum) to part 0 through LDS
+    __syncthreads(); // every wave is done with the tiles
+    float* sm = (float*)smem;
+    if (kq > 0 && wave_active) {
+        float* dst = sm + ((kq - 1) * NRB + rbw) * MERGE_FLOATS + lane;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) dst[(db * 16 + q) * 64] = acc[db][q];
+        dst[(DB * 16) * 64] = m2;
+        dst[(DB * 16 + 1) * 64] = lsum;
+    }
+    __syncthreads();
+    if (kq > 0 || !wave_active) return;
+#pragma unroll
+    for (int o = 1; o < KQ; ++o) {
+        const float* src = sm + ((o - 1) * NRB + rbw) * MERGE_FLOATS + lane;
+        const float mo = src[(DB * 16) * 64], lo = src[(DB * 16 + 1) * 64];
+        const float M = fmaxf(m2, mo);
+        if (M == -INFINITY) continue; // neither part has seen a visible key
+        const float fa = __builtin_amdgcn_exp2f(m2 - M), fb = __builtin_amdgcn_exp2f(mo - M); // exp2(-inf) = 0
+        lsum = lsum * fa + lo * fb;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[db][q] = acc[db][q] * fa + src[(db * 16 + q) * 64] * fb;
+        m2 = M;
+    }
+
+    // ---- epilogue: lane (col, half) holds, for row `col`, channels db*32 + 8*(q/4) + 4*half + q%4
+    const int r_local = row_base + col;
+    const float l = half_sum(lsum);
+    if (p.num_splits == 1) {
+        if (r_local >= p.rows) return;
+        uint16_t* o = (uint16_t*)p.out + (((int64_t)b * p.T + node) * p.Hq + hq) * D;
+        const float inv = 1.f / l;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                u32x2 w;
+                w[0] = pack_bf16x2(acc[db][4 * q4] * inv, acc[db][4 * q4 + 1] * inv);
+                w[1] = pack_bf16x2(acc[db][4 * q4 + 2] * inv, acc[db][4 * q4 + 3] * inv);
+                *(u32x2*)(o + db * 32 + 8 * q4 + 4 * half) = w;
+            }
+    } else {
+        const int64_t blk = part_block(p, (int64_t)b * p.Hkv + kvh, split, row_base >> 5);
+        uint16_t* po = p.part_o + blk * (kRowBlock * D) + lane * 4;
+        const float inv = l > 0.f ? 1.f / l : 0.f; // no visible key in this split: zeros, weight 0
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *(u32x2*)(po + (db * 4 + q4) * 256) = pack_partial(acc[db][4 * q4], acc[db][4 * q4 + 1], acc[db][4 * q4 + 2],
+                                                                  acc[db][4 * q4 + 3], inv);
+        if (half == 0) {
+            const f32x2 ml = {m2, l};
+            const int64_t mlb = ml_block(p, (int64_t)b * p.Hkv + kvh, split, row_base >> 5);
+            *(f32x2*)(p.part_ml + (mlb + col) * 2) = ml;
+        }
+    }
+}
+
+template <int D, int NRB>
+hipError_t launch_res(const AttnParams& p, hipStream_t s) {
+    const dim3 grid(((p.total_wgs + 7) / 8) * 8);
+    hipLaunchKernelGGL((attn_mfma_resident_kernel<D, NRB>), grid, dim3(kResWaves * kWave), 0, s, p);
+    return hipGetLastError();
+}
+
+} // namespace
+
+// Row blocks per workgroup: 4, 2 or 1 (the other waves split the keys).
+bool attention_resident_supported(int row_blocks) { return row_blocks == 4 || row_blocks == 2 || row_blocks == 1; }
+
+hipError_t launch_attention_mfma_resident(const AttnParams& p, int row_blocks, hipStream_t s) {
+    if (!attention_resident_supported(row_blocks) || p.keys_per_split > kResidentMaxKeys) return hipErrorInvalidValue;
+    if (p.d == 128) {
+        return row_blocks == 4 ? launch_res<128, 4>(p, s) : (row_blocks == 2 ? launch_res<128, 2>(p, s) : launch_res<128, 1>(p, s));
+    }
+    if (p.d == 64) {
+        return row_blocks == 4 ? launch_res<64, 4>(p, s) : (row_blocks == 2 ? launch_res<64, 2>(p, s) : launch_res<64, 1>(p, s));
+    }
+    return hipErrorInvalidValue;
+}
+
+} // namespace vs

@@ -18,14 +18,11 @@ constexpr int wait_vm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 constexpr float kLazy = 8.f; // log2 slack of the running softmax reference
 
-// max(a, b, c) as one instruction. (fmaxf chains first pass every operand through a
-// canonicalising v_max x, x because the compiler cannot prove MFMA results are not
-// signalling NaNs; the hardware instruction itself handles them.)
-__device__ __forceinline__ float max3(float a, float b, float c) {
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
+// max(a, b, c); chains of these become v_max3_f32. (Not inline assembly: the compiler pads
+// the wait states an MFMA result needs before a vector instruction may read it only for
+// instructions it can see, and an asm statement reading a fresh MFMA result returned stale
+// registers now and then - run-to-run differences in the softmax reference.)
+__device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
 // max / sum over the two 32-lane halves, result in every lane (v_permlane32_swap)
 __device__ __forceinline__ float half_max(float x) {

@@ -14,6 +14,7 @@ constexpr int kIterKeys = 64;   // keys staged in LDS per loop iteration (two sc
 constexpr int kRowBlock = 32;   // query rows per MFMA row block
 constexpr int kMaxWaves = 8;    // waves per workgroup in the MFMA attention kernel
 constexpr int kArgmaxBlock = 256;
+constexpr int kResidentMaxKeys = 256; // keys of one split that the resident attention kernel keeps in LDS
 
 // Everything the attention kernels need, passed by value.
 struct AttnParams {
@@ -157,6 +158,8 @@ hipError_t launch_attention_generic(const AttnParams& p, int dtype, hipStream_t 
 hipError_t launch_attention_mfma(const AttnParams& p, int rpw, int waves, hipStream_t s);
 bool attention_pipe_supported(int rpw, int waves);
 hipError_t launch_attention_mfma_pipe(const AttnParams& p, int rpw, int waves, hipStream_t s);
+bool attention_resident_supported(int row_blocks);
+hipError_t launch_attention_mfma_resident(const AttnParams& p, int row_blocks, hipStream_t s);
 hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_accept_sample(const SampleParams& p, hipStream_t s);

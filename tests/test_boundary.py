@@ -70,7 +70,9 @@ def _desc(**kw):
     ({"paged": 1, "block_size": 24, "max_blocks": 200, "num_blocks": 300, "block_table": 4096}, -6),
     ({"paged": 1, "block_size": 16, "max_blocks": 10, "num_blocks": 300, "block_table": 4096}, -6),
     ({"num_splits": -1}, -2),
-    ({"schedule": 3}, -2), ({"schedule": vs.VS_SCHED_PIPELINED, "rows_per_wave": 2}, -2),
+    ({"schedule": 4}, -2), ({"schedule": vs.VS_SCHED_PIPELINED, "rows_per_wave": 2}, -2),
+    ({"schedule": vs.VS_SCHED_RESIDENT}, 0), ({"schedule": vs.VS_SCHED_RESIDENT, "rows_per_wave": 2}, -2),
+    ({"schedule": vs.VS_SCHED_RESIDENT, "waves_per_group": 4}, -2),
     ({"schedule": vs.VS_SCHED_PIPELINED, "waves_per_group": 2}, -2),
     ({"schedule": vs.VS_SCHED_PIPELINED, "waves_per_group": 4}, 0), ({"schedule": vs.VS_SCHED_LOOP}, 0),
 ])
@@ -82,15 +84,30 @@ def test_attention_descriptor_validation(kw, code):
 
 
 def test_plan_and_workspace_sizes():
-    # one layer of one sequence: small workgroups, one row block per wave, many splits
+    # one layer of one short sequence: LDS-resident splits of 256 keys, four row blocks per workgroup
     rc, plan = vs.vs_attention_plan(_desc())
-    assert rc == 0 and plan.impl == vs.VS_IMPL_MFMA
-    assert plan.rows_per_wave == 1 and plan.waves_per_group == 4 and plan.row_groups == 4
-    assert plan.keys_per_split % 64 == 0 and plan.num_splits * plan.keys_per_split >= 1696 + 60
+    assert rc == 0 and plan.impl == vs.VS_IMPL_MFMA and plan.schedule == vs.VS_SCHED_RESIDENT
+    assert plan.rows_per_wave == 1 and plan.waves_per_group == 8 and plan.row_groups == 4
+    assert plan.keys_per_split == 256 and plan.num_splits == 7
     assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
     ws = vs.vs_attention_workspace_bytes(_desc())
     assert ws >= 4 * plan.num_splits * 448 * (128 * 2 + 2 * 4)          # fp16 partial rows + fp32 (max, sum)
-    assert plan.schedule == vs.VS_SCHED_LOOP
+    # ... the streaming loop when asked for, or when the caller's knobs rule the resident kernel out
+    rc, plan = vs.vs_attention_plan(_desc(schedule=vs.VS_SCHED_LOOP))
+    assert plan.schedule == vs.VS_SCHED_LOOP and plan.rows_per_wave == 1 and plan.waves_per_group == 4 and plan.row_groups == 4
+    assert plan.keys_per_split % 64 == 0 and plan.num_splits * plan.keys_per_split >= 1696 + 60
+    assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
+    assert vs.vs_attention_plan(_desc(waves_per_group=4))[1].schedule == vs.VS_SCHED_LOOP
+    assert vs.vs_attention_plan(_desc(num_splits=2))[1].schedule == vs.VS_SCHED_LOOP
+    # ... and for long sequences or two row blocks (MHA)
+    one_long = _desc(max_prefix_len=6684, capacity=6800, stride_head=6800 * 128)
+    assert vs.vs_attention_plan(one_long)[1].schedule == vs.VS_SCHED_LOOP
+    one_mha = _desc(Hq=32, Hkv=32, stride_seq=32 * 1800 * 128)
+    assert vs.vs_attention_plan(one_mha)[1].schedule == vs.VS_SCHED_LOOP
+    # an explicit resident schedule caps a split at 256 keys whatever split count is asked for
+    rc, pr = vs.vs_attention_plan(_desc(schedule=vs.VS_SCHED_RESIDENT, num_splits=1, max_prefix_len=6684, capacity=6800,
+                                        stride_head=6800 * 128))
+    assert pr.keys_per_split == 256 and pr.num_splits == 27
     # many units: pipelined kernel, eight waves, rows split over two workgroups, no key split, no combine
     big = _desc(B=28, stride_seq=4 * 1800 * 128)
     rc, pb = vs.vs_attention_plan(big)

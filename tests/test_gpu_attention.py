@@ -72,6 +72,10 @@ def test_full_size_single_sequence(gu, oracle_mod, name):
             got_p, _, dp = _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=sp, waves_per_group=nw,
                                           schedule=vs.VS_SCHED_PIPELINED)
             assert dp.plan().schedule == vs.VS_SCHED_PIPELINED
+    # the LDS-resident schedule: planner's split count, splits of one, two and four 64-key tiles
+    for sp in (0, 10 ** 6, (inp.cfg.prefix[0] + inp.cfg.T + 127) // 128, 1):
+        _, _, dr = _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=sp, schedule=vs.VS_SCHED_RESIDENT)
+        assert dr.plan().schedule == vs.VS_SCHED_RESIDENT and dr.plan().keys_per_split <= 256
     _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
 
 
@@ -84,6 +88,8 @@ def test_c5_ragged_paged_batch(gu, oracle_mod):
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=2, rows_per_wave=1, waves_per_group=4)
     for nw, sp in ((8, 1), (8, 2), (4, 5)):   # paged copies in the pipelined kernel
         _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=sp, waves_per_group=nw, schedule=vs.VS_SCHED_PIPELINED)
+    for sp in (0, 11):                        # ... and in the resident one
+        _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=sp, schedule=vs.VS_SCHED_RESIDENT)
 
 
 def test_layers_folded_into_batch(gu, oracle_mod):
@@ -98,6 +104,7 @@ def test_layers_folded_into_batch(gu, oracle_mod):
     # and the straight-loop alternatives
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=1, rows_per_wave=1, waves_per_group=8, schedule=vs.VS_SCHED_LOOP)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=2, rows_per_wave=2, waves_per_group=8)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, schedule=vs.VS_SCHED_RESIDENT)
 
 
 # ---------------------------------------------------------------- fuzz over shapes
@@ -129,6 +136,7 @@ def test_fuzz_shapes(gu, oracle_mod, d, g, hkv, paged, T, S, splits, B, k):
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits, rows_per_wave=1 + k % 2, waves_per_group=[8, 1, 4, 2][k % 4])
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits, waves_per_group=[4, 8][k % 2], schedule=vs.VS_SCHED_PIPELINED)
+    _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=splits, schedule=vs.VS_SCHED_RESIDENT)
     _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
 
 
@@ -149,6 +157,7 @@ def test_tree_dominated_no_prefix(gu, oracle_mod):
         inp = gen.attention_inputs(cfg, 40 + T)
         _run_and_check(gu, oracle_mod, inp)
         _run_and_check(gu, oracle_mod, inp, schedule=vs.VS_SCHED_PIPELINED)
+        _run_and_check(gu, oracle_mod, inp, schedule=vs.VS_SCHED_RESIDENT)
         _run_and_check(gu, oracle_mod, inp, impl=vs.VS_IMPL_GENERIC)
 
 
@@ -163,7 +172,7 @@ def test_mask_from_mask_build_equals_internal(gu, oracle_mod):
 
 
 @pytest.mark.parametrize("impl,sched", [(vs.VS_IMPL_MFMA, vs.VS_SCHED_LOOP), (vs.VS_IMPL_MFMA, vs.VS_SCHED_PIPELINED),
-                                        (vs.VS_IMPL_GENERIC, 0)])
+                                        (vs.VS_IMPL_MFMA, vs.VS_SCHED_RESIDENT), (vs.VS_IMPL_GENERIC, 0)])
 def test_needles(gu, oracle_mod, impl, sched):
     """A huge key on a NON-ancestor tree slot must not move a node's output; the same key
     on an ancestor slot must pull the output to that slot's value."""
@@ -253,6 +262,10 @@ def test_paged_equals_contiguous_bitwise(gu, oracle_mod):
     # the pipelined kernel: paged copies take the general path, contiguous ones the fast path
     kw = dict(num_splits=2, waves_per_group=8, schedule=vs.VS_SCHED_PIPELINED)
     assert np.array_equal(gu.DeviceAttn(inp, **kw).run(), gu.DeviceAttn(inp2, **kw).run())
+    # the resident kernel: the contiguous cache is NaN past each sequence's end, which its
+    # copies read (they start before the sequence's length is known) and must discard
+    kw = dict(num_splits=0, schedule=vs.VS_SCHED_RESIDENT)
+    assert np.array_equal(gu.DeviceAttn(inp, **kw).run(), gu.DeviceAttn(inp2, **kw).run())
 
 
 def test_deterministic_and_untouched_guards(gu):
@@ -266,12 +279,30 @@ def test_deterministic_and_untouched_guards(gu):
     assert np.isfinite(b).all()
 
 
+@pytest.mark.parametrize("sched,kw", [
+    (vs.VS_SCHED_LOOP, {}), (vs.VS_SCHED_LOOP, {"rows_per_wave": 2, "waves_per_group": 8, "num_splits": 2}),
+    (vs.VS_SCHED_PIPELINED, {"waves_per_group": 8}), (vs.VS_SCHED_PIPELINED, {"waves_per_group": 4, "num_splits": 3}),
+    (vs.VS_SCHED_RESIDENT, {}), (vs.VS_SCHED_RESIDENT, {"num_splits": 10 ** 6}),
+])
+@pytest.mark.parametrize("B,S", [(1, 50), (1, 1696), (4, 700)])
+def test_repeated_runs_bit_identical(gu, sched, kw, B, S):
+    """Nothing in a kernel may depend on timing: the same launch gives the same bits every time
+    (plain tiles, masked tiles, the merge of key parts and the split combine all take part)."""
+    cfg = dataclasses.replace(gen.CONFIGS["C3"], B=B, prefix=[S - 13 * b for b in range(B)])
+    da = gu.DeviceAttn(gen.attention_inputs(cfg, 48), schedule=sched, **kw)
+    first = da.run().copy()
+    assert np.isfinite(first).all()
+    for rep in range(5):
+        assert np.array_equal(da.run(), first), f"run {rep + 2} differs from the first"
+
+
 def test_max_prefix_bound_larger_than_actual(gu, oracle_mod):
     """The host bound only sizes the launch: splits past a sequence's end are empty."""
     cfg = dataclasses.replace(gen.CONFIGS["C3"], prefix=[130])
     inp = gen.attention_inputs(cfg, 46, extra_cap=4000)
     _run_and_check(gu, oracle_mod, inp, max_prefix_len=3000, num_splits=9)
     _run_and_check(gu, oracle_mod, inp, max_prefix_len=3000, num_splits=9, schedule=vs.VS_SCHED_PIPELINED)
+    _run_and_check(gu, oracle_mod, inp, max_prefix_len=3000, schedule=vs.VS_SCHED_RESIDENT)
 
 
 # ---------------------------------------------------------------- data-dependent errors
@@ -283,7 +314,8 @@ def test_status_reports_bad_inputs_without_faulting(gu):
     inp.parent[1] = [-1, 0, 2, 1, 0, 0]            # parent[2] = 2 is not < 2
     inp.prefix_len[2] = 10 ** 6                    # beyond the cache
     inp.block_table[3, 0] = 10 ** 7                # outside the pool
-    for impl, sched in ((vs.VS_IMPL_MFMA, vs.VS_SCHED_LOOP), (vs.VS_IMPL_MFMA, vs.VS_SCHED_PIPELINED), (vs.VS_IMPL_GENERIC, 0)):
+    for impl, sched in ((vs.VS_IMPL_MFMA, vs.VS_SCHED_LOOP), (vs.VS_IMPL_MFMA, vs.VS_SCHED_PIPELINED),
+                        (vs.VS_IMPL_MFMA, vs.VS_SCHED_RESIDENT), (vs.VS_IMPL_GENERIC, 0)):
         da = gu.DeviceAttn(inp, impl=impl, max_prefix_len=60, schedule=sched)
         da.run()
         st = da.status.cpu().numpy()
