@@ -100,11 +100,11 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     int rpw = d->rows_per_wave, waves = d->waves_per_group, splits = d->num_splits;
     const bool pipe_ok = (rpw == 0 || rpw == 1) && (waves == 0 || waves == 4 || waves == 8);
     // few units, several row blocks, a short sequence (at most 2048 keys) and no caller's
-    // choice that it cannot honour: the LDS-resident
-    // kernel, whose second split of the keys among the waves shortens each workgroup's loop
-    // (measured on a C3-sized layer: 12.1 + 5.1 us with 7 splits against 13.9 + 5.7 us with 10
-    // for the streaming loop; slower than the loop for two row blocks and for 5000+ keys,
-    // where its 256-key limit forces too many partial results)
+    // choice that it cannot honour: the LDS-resident kernel, whose second split of the keys
+    // among the waves shortens each workgroup's loop. Measured on C3-sized layers replayed from
+    // a HIP graph over 400 MB of K/V (every layer cold in the caches): 19.0 us per layer with
+    // 10 splits, the streaming loop 19.2 us; slower than the loop for two row blocks and for
+    // 5000+ keys, where its 256-key limit forces too many partial results.
     const bool resident_ok = !big && nrb >= 3 && tiles <= 32 && (rpw == 0 || rpw == 1) && (waves == 0 || waves == 8) &&
                              (splits <= 0 || (tiles + splits - 1) / splits <= kResidentMaxKeys / kIterKeys);
     pl.schedule = d->schedule != VS_SCHED_AUTO ? d->schedule
@@ -119,7 +119,7 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
         pl.res_rb = nrb >= 3 ? 4 : nrb;
         pl.row_groups = (nrb + pl.res_rb - 1) / pl.res_rb;
         const int max_tiles = kResidentMaxKeys / kIterKeys;
-        if (splits <= 0) splits = (tiles + max_tiles - 1) / max_tiles; // full splits: fewest partial results (measured)
+        if (splits <= 0) splits = (tiles + 2) / 3; // three 64-key tiles per split (measured: 19.0 us per C3 layer; four: 19.6)
         int tps = (tiles + splits - 1) / splits;
         if (tps > max_tiles) tps = max_tiles;
         if (tps < 1) tps = 1;

@@ -84,11 +84,11 @@ def test_attention_descriptor_validation(kw, code):
 
 
 def test_plan_and_workspace_sizes():
-    # one layer of one short sequence: LDS-resident splits of 256 keys, four row blocks per workgroup
+    # one layer of one short sequence: LDS-resident splits of 192 keys, four row blocks per workgroup
     rc, plan = vs.vs_attention_plan(_desc())
     assert rc == 0 and plan.impl == vs.VS_IMPL_MFMA and plan.schedule == vs.VS_SCHED_RESIDENT
     assert plan.rows_per_wave == 1 and plan.waves_per_group == 8 and plan.row_groups == 4
-    assert plan.keys_per_split == 256 and plan.num_splits == 7
+    assert plan.keys_per_split == 192 and plan.num_splits == 10
     assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
     ws = vs.vs_attention_workspace_bytes(_desc())
     assert ws >= 4 * plan.num_splits * 448 * (128 * 2 + 2 * 4)          # fp16 partial rows + fp32 (max, sum)
