@@ -66,23 +66,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     const int kvh = rest % p.Hkv;
     const int b = rest / p.Hkv;
 
-    const int32_t S = p.prefix_len[b]; // requested before the tree is read: one latency, not two
-    int32_t tree_code = VS_STATUS_OK;
-    if (p.tree_mask || p.tree_keys == 0) {
-        if (tid == 0) sflag = 0;
-        __syncthreads();
-    } else {
-        tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
-    }
-    const bool s_ok = prefix_ok(p, S);
-    if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
-    if (tree_code != VS_STATUS_OK || !s_ok) return;
-
-    const int nk = S + p.tree_keys;
-    const int k0 = split * p.keys_per_split;
-    if (k0 >= nk) return;
-    const int k1 = min(nk, k0 + p.keys_per_split);
-    const int n = (k1 - k0 + kTileKeys - 1) / kTileKeys; // tiles of this split
+    const int32_t S = p.prefix_len[b]; // requested first, needed last: the first tiles and the queries are requested before it arrives
+    const int k0 = split * p.keys_per_split; // the host keeps k0 below max_prefix_len + tree_keys, hence inside the cache
 
     // ---- tile copies. One load instruction of a wave fetches 1 KB of consecutive memory:
     // RPI whole rows (tokens) of D channels, lane q -> row q / LPR, 16-byte chunk q % LPR, so
@@ -109,6 +94,74 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
         k_st[j] = (uint32_t)(((r >> 4) * DB + (c >> 2)) * 1024 + (c & 3) * 256 + (((r & 15) ^ (4 * (c & 3))) * 16));
         v_st[j] = (uint32_t)(((r >> 4) * DB + (c >> 2)) * 1024 + (4 * (r & 15) + (c & 3)) * 16);
     }
+    u32x4 stage[2][4][BPW];
+    // The first four tiles - K(0), K(1), K(2), V(0), through register set 1 - are requested before
+    // the prefix length is known: clamped to the cache instead of the sequence, and rows that
+    // turn out to lie past the sequence's last key are zeroed when the tiles go into LDS
+    // (whatever the cache holds there, NaN included, must not meet a zero probability).
+    {
+        const int64_t cache_tokens = p.paged ? (int64_t)p.max_blocks * p.block_size : p.capacity;
+        const int kend = (int)(cache_tokens < (int64_t)k0 + p.keys_per_split ? cache_tokens : (int64_t)k0 + p.keys_per_split);
+        auto load_tile_early = [&](auto is_v, int t, u32x4(&r)[BPW]) __attribute__((always_inline)) {
+            const uint16_t* gbase = decltype(is_v)::value ? vbase : kbase;
+#pragma unroll
+            for (int j = 0; j < BPW; ++j) {
+                const int i = wave * BPW + j;
+                if (NW * BPW == BPS || i < BPS) {
+                    const int r0 = min(k0 + t * kTileKeys + RPI * i, kend - 1); // RPI divides 16: one cache block in paged mode
+                    int tok = min(r0 + lrow, kend - 1);
+                    int64_t base = head_base;
+                    if (p.paged) {
+                        int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (r0 >> p.block_shift)];
+                        if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
+                        base += (int64_t)blk * p.stride_block;
+                        tok &= p.block_size - 1;
+                    }
+                    r[j] = *(const u32x4*)(gbase + base + (uint32_t)(tok * stride_tok + lchunk * 8));
+                }
+            }
+        };
+        load_tile_early(std::false_type{}, 0, stage[1][0]);
+        load_tile_early(std::false_type{}, 1, stage[1][1]);
+        load_tile_early(std::false_type{}, 2, stage[1][2]);
+        load_tile_early(std::true_type{}, 0, stage[1][3]);
+    }
+
+    // ---- this wave's rows and queries (in flight together with the first tiles)
+    const int row_base = rg * p.rows_per_group + wave * (RPW * kRowBlock);
+    const bool wave_active = row_base < p.rows;
+    bf16x8 qf[RPW][KS];
+    int node_of[RPW];
+#pragma unroll
+    for (int rb = 0; rb < RPW; ++rb) {
+        // rows past the end repeat the last row (finite data, results discarded)
+        const int r = min(row_base + rb * kRowBlock + col, p.rows - 1);
+        const int node = r / p.group;
+        const int hq = kvh * p.group + (r - node * p.group);
+        node_of[rb] = node;
+        const uint16_t* qr = (const uint16_t*)p.q + (((int64_t)b * p.T + node) * p.Hq + hq) * D + half * 8;
+        if (wave_active) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) qf[rb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qr + ks * 16));
+        }
+    }
+
+    int32_t tree_code = VS_STATUS_OK;
+    if (p.tree_mask || p.tree_keys == 0) {
+        if (tid == 0) sflag = 0;
+        __syncthreads();
+    } else {
+        tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
+    }
+    const bool s_ok = prefix_ok(p, S);
+    if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
+    if (tree_code != VS_STATUS_OK || !s_ok) return;
+
+    const int nk = S + p.tree_keys;
+    if (k0 >= nk) return;
+    const int k1 = min(nk, k0 + p.keys_per_split);
+    const int n = (k1 - k0 + kTileKeys - 1) / kTileKeys; // tiles of this split
+
     const int n_full = (k1 - k0) / kTileKeys; // tiles without a ragged end
     // first key of the split in this (sequence, KV head) slice; only used when not paged
     const char* kfast = (const char*)(kbase + head_base + (int64_t)k0 * stride_tok);
@@ -160,7 +213,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // Copies are grouped per iteration: group g = K(2g+3), K(2g+4), V(2g+1), V(2g+2) is what
     // iteration g writes to LDS. Its loads are issued in iteration g - 2, so two groups are
     // in flight and alternate between two register sets.
-    u32x4 stage[2][4][BPW];
     auto load_group = [&](auto lfast_tag, auto set_tag, int g) __attribute__((always_inline)) {
         constexpr int SET = decltype(set_tag)::value;
         load_tile(lfast_tag, std::false_type{}, 2 * g + 3, stage[SET][0]);
@@ -176,32 +228,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
         stash_tile(std::true_type{}, sV[(2 * g + 2) & 3], stage[SET][3]);
     };
 
-    // prologue copies: K(0), K(1), K(2) and V(0) (through set 1), and group 0 (set 0)
-    load_tile(std::false_type{}, std::false_type{}, 0, stage[1][0]);
-    load_tile(std::false_type{}, std::false_type{}, 1, stage[1][1]);
-    load_tile(std::false_type{}, std::false_type{}, 2, stage[1][2]);
-    load_tile(std::false_type{}, std::true_type{}, 0, stage[1][3]);
+    // the rest of the prologue copies: group 0 (set 0)
     load_group(std::false_type{}, std::integral_constant<int, 0>{}, 0);
 
-    // ---- this wave's rows, their masks and queries
-    const int row_base = rg * p.rows_per_group + wave * (RPW * kRowBlock);
-    const bool wave_active = row_base < p.rows;
     uint64_t mask[RPW];
-    bf16x8 qf[RPW][KS];
-    const uint16_t* qbase = (const uint16_t*)p.q;
 #pragma unroll
-    for (int rb = 0; rb < RPW; ++rb) {
-        // rows past the end repeat the last row (finite data, results discarded)
-        const int r = min(row_base + rb * kRowBlock + col, p.rows - 1);
-        const int node = r / p.group;
-        const int hq = kvh * p.group + (r - node * p.group);
-        mask[rb] = p.tree_keys == 0 ? 0ull : (p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : ancestor_mask(sp, node));
-        const uint16_t* qr = qbase + (((int64_t)b * p.T + node) * p.Hq + hq) * D + half * 8;
-        if (wave_active) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) qf[rb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qr + ks * 16));
-        }
-    }
+    for (int rb = 0; rb < RPW; ++rb)
+        mask[rb] = p.tree_keys == 0 ? 0ull : (p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node_of[rb]] : ancestor_mask(sp, node_of[rb]));
 
     float m2[RPW], lsum[RPW]; // running reference (log2 domain, scaled) and this lane's share of the sum
     f32x16 acc[RPW][DB];
@@ -459,10 +492,25 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // outside any branch, also keeps the compiler from re-waiting for the query registers
     // inside the loop, where such a wait would drain the tile copies in flight.
     __builtin_amdgcn_s_waitcnt(wait_vm(0));
-    stash_tile(std::false_type{}, sK[0], stage[1][0]);
-    stash_tile(std::false_type{}, sK[1], stage[1][1]);
-    stash_tile(std::false_type{}, sK[2], stage[1][2]);
-    stash_tile(std::true_type{}, sV[0], stage[1][3]);
+    {
+        // the early tiles: rows at or past k1 become zeros
+        auto stash_tile_live = [&](auto is_v, uint16_t* slot, const u32x4(&r)[BPW], int t) __attribute__((always_inline)) {
+            constexpr bool ISV = decltype(is_v)::value;
+#pragma unroll
+            for (int j = 0; j < BPW; ++j) {
+                const int i = wave * BPW + j;
+                if (NW * BPW == BPS || i < BPS) {
+                    const bool live = k0 + t * kTileKeys + RPI * i + lrow < k1;
+                    const u32x4 zero = {0u, 0u, 0u, 0u};
+                    *(u32x4*)((char*)slot + (ISV ? v_st[j] : k_st[j])) = live ? r[j] : zero;
+                }
+            }
+        };
+        stash_tile_live(std::false_type{}, sK[0], stage[1][0], 0);
+        stash_tile_live(std::false_type{}, sK[1], stage[1][1], 1);
+        stash_tile_live(std::false_type{}, sK[2], stage[1][2], 2);
+        stash_tile_live(std::true_type{}, sV[0], stage[1][3], 0);
+    }
     load_group(std::false_type{}, std::integral_constant<int, 1>{}, 1);
     __syncthreads();
 
