@@ -154,7 +154,9 @@ typedef struct vs_attn_desc {
     int32_t rows_per_wave;  /* MFMA path: 32-row blocks per wave, 1 or 2; 0 = choose */
     int32_t waves_per_group; /* MFMA path: waves per workgroup, 1, 2, 4 or 8; 0 = choose */
     int32_t schedule;       /* MFMA path: vs_attn_schedule; PIPELINED needs rows_per_wave 0 or 1
-                               and waves_per_group 0, 4 or 8 */
+                               and waves_per_group 0, 4 or 8; RESIDENT needs rows_per_wave 0 or 1 and
+                               waves_per_group 0 or 8, and never puts more than 256 keys into a split
+                               (num_splits is raised where it asks for more) */
 } vs_attn_desc;
 
 /* What a call with this descriptor would launch (for tests and reports). */
@@ -167,7 +169,7 @@ typedef struct vs_attn_plan {
     int32_t rows_per_wave;   /* 32-row blocks per wave (MFMA path) */
     int32_t workgroups;      /* main kernel grid size */
     int32_t combine;         /* 1 if a split-combine kernel follows */
-    int32_t schedule;        /* VS_SCHED_LOOP or VS_SCHED_PIPELINED (MFMA path), else 0 */
+    int32_t schedule;        /* VS_SCHED_LOOP, VS_SCHED_PIPELINED or VS_SCHED_RESIDENT (MFMA path), else 0 */
 } vs_attn_plan;
 
 int32_t vs_attention_plan(const vs_attn_desc* desc, vs_attn_plan* plan); /* both host */
