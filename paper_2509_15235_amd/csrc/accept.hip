@@ -109,35 +109,37 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = p.T;
+    // four threads per row share the row's chunk results (T <= 64 rows, 256 threads). Nothing here
+    // depends on the tree, so everything is requested before the tree is waited for (one memory
+    // round trip instead of two): the row's first logit (NaN rule), the draft tokens, and sixteen
+    // chunk results per thread (all of them for vocabularies up to 64 chunks).
+    constexpr int kPre = 16;
+    const int i = tid >> 2, sub = tid & 3;
+    const int64_t row = (int64_t)b * T + i;
+    const float* pv = p.part_val + row * p.chunks;
+    const int32_t* pi = p.part_idx + row * p.chunks;
+    float v[kPre];
+    int32_t x[kPre];
+    auto fetch = [&](int c0) {
+#pragma unroll
+        for (int q = 0; q < kPre; ++q) {
+            const int c = c0 + 4 * q;
+            const bool ok = i < T && c < p.chunks;
+            v[q] = ok ? pv[c] : -INFINITY;
+            x[q] = ok ? pi[c] : INT32_MAX;
+        }
+    };
+    fetch(sub);
+    const float first = (i < T && sub == 0) ? p.logits[row * p.ld] : 0.f;
+    const int32_t draft_own = (tid < T) ? p.draft[(int64_t)b * T + tid] : -1;
     const int32_t tree_code = load_tree(p.parent + (int64_t)b * T, T, sp, &sflag);
-
-    // four threads per row share the row's chunk results (T <= 64 rows, 256 threads)
+    if (tid < T) sdraft[tid] = draft_own;
     {
-        const int i = tid >> 2, sub = tid & 3;
         Best best = {-INFINITY, INT32_MAX};
-        // requested now, used after the merge: the row's first logit (NaN rule) and the draft tokens
-        const float first = (i < T && sub == 0) ? p.logits[((int64_t)b * T + i) * p.ld] : 0.f;
-        if (tid < T) sdraft[tid] = p.draft[(int64_t)b * T + tid];
-        {
-            // sixteen chunk results per thread are requested before the first compare: one memory
-            // round trip for vocabularies up to 64 chunks
-            constexpr int kPre = 16;
-            const int64_t row = (int64_t)b * T + i;
-            const float* pv = p.part_val + row * p.chunks;
-            const int32_t* pi = p.part_idx + row * p.chunks;
-            for (int c0 = sub; c0 < p.chunks; c0 += 4 * kPre) {
-                float v[kPre];
-                int32_t x[kPre];
+        for (int c0 = sub; c0 < p.chunks; c0 += 4 * kPre) {
+            if (c0 != sub) fetch(c0);
 #pragma unroll
-                for (int q = 0; q < kPre; ++q) {
-                    const int c = c0 + 4 * q;
-                    const bool ok = i < T && c < p.chunks;
-                    v[q] = ok ? pv[c] : -INFINITY;
-                    x[q] = ok ? pi[c] : INT32_MAX;
-                }
-#pragma unroll
-                for (int q = 0; q < kPre; ++q) take(best, v[q], x[q]);
-            }
+            for (int q = 0; q < kPre; ++q) take(best, v[q], x[q]);
         }
 #pragma unroll
         for (int o = 1; o <= 2; o <<= 1) {
@@ -148,7 +150,6 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
         if (i < T && sub == 0) {
             // what a left-to-right '>' scan returns: a NaN in column 0 is never displaced,
             // and a row with nothing above -inf keeps index 0
-            const int64_t row = (int64_t)b * T + i;
             int32_t idx = best.i;
             if (first != first || idx == INT32_MAX) idx = 0;
             samax[i] = idx;

@@ -20,6 +20,7 @@ namespace {
 
 constexpr int kVec = 4;                  // 16-byte loads per thread and chunk (chunk = 4096 floats)
 constexpr int kWalkThreads = 256;
+constexpr int kKeepStats = 4096;          // (max, sum) pairs the walk kernel can keep in LDS (32 KB)
 constexpr int kPerThread = 16;           // chunk elements per thread of the walk kernel
 static_assert(kWalkThreads * kPerThread == 4096, "the walk kernel scans one 4096-float chunk at a time");
 
@@ -85,7 +86,8 @@ __global__ __launch_bounds__(kArgmaxBlock) void softmax_stats_partial_kernel(con
 // masses, the uniforms, every candidate's weight in its parent's row), so a step of the walk
 // costs no memory round trip: removing a rejected token just lowers the row's mass. Only when
 // that subtraction would cancel (the rejected token held > 95 % of the mass), and once at the
-// end for the bonus draw, the row's per-chunk masses are brought into LDS.
+// end for the bonus draw, the row's per-chunk masses are needed - from the copy of all rows'
+// chunk statistics in LDS when those fit, else from memory.
 __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const SampleParams p) {
     __shared__ int32_t sp[VS_MAX_TREE];
     __shared__ int32_t sflag;
@@ -98,15 +100,36 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
     __shared__ float sremoved_ex[VS_MAX_TREE];
     __shared__ float sred[kWalkThreads / kWave];
     __shared__ float sch[kMaxSampleChunks]; // residual weight per chunk of the current row
+    __shared__ float skeep_m[kKeepStats], skeep_s[kKeepStats]; // every row's chunk statistics, when they fit
     __shared__ int32_t spick, slast;
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int T = p.T;
-    const float u_bonus = p.u_bonus[b]; // requested now, used at the very end
-    const int32_t tree_code = load_tree(p.parent + (int64_t)b * T, T, sp, &sflag);
-    // node tid's draft token and its logit in the parent's row (parent index clamped: a malformed
-    // tree is reported below and must not steer a load out of bounds)
+    // Everything that does not depend on the tree is requested before the tree is waited for: the
+    // bonus uniform (used at the very end), this thread's draft token and acceptance uniform, and
+    // the first sixteen chunk statistics of this thread's row (four threads per row; one memory
+    // round trip covers vocabularies up to 64 chunks). Malformed trees are reported below; none
+    // of these addresses depends on the tree's contents.
+    const float u_bonus = p.u_bonus[b];
+    constexpr int kPre = 16;
+    const int ri = tid >> 2, sub = tid & 3;
+    const int64_t rrow = (int64_t)b * T + ri;
+    float pm[kPre], ps[kPre];
+    auto fetch_stats = [&](int c0) {
+#pragma unroll
+        for (int q = 0; q < kPre; ++q) {
+            const int c = c0 + 4 * q;
+            const bool ok = ri < T && c < p.chunks;
+            pm[q] = ok ? p.part_m[rrow * p.chunks + c] : -INFINITY;
+            ps[q] = ok ? p.part_s[rrow * p.chunks + c] : 0.f;
+        }
+    };
+    fetch_stats(sub);
     const int32_t x_own = (tid < T) ? p.draft[(int64_t)b * T + tid] : -1;
+    const float u_own = (tid < T) ? p.u_accept[(int64_t)b * T + tid] : 0.f;
+    const int32_t tree_code = load_tree(p.parent + (int64_t)b * T, T, sp, &sflag);
+    // node tid's logit in the parent's row (parent index clamped: a malformed tree is reported
+    // below and must not steer a load out of bounds)
     const bool has_logit = tid >= 1 && tid < T && x_own >= 0 && x_own < p.V;
     float l_own = 0.f;
     if (has_logit) {
@@ -114,21 +137,23 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
         l_own = p.logits[((int64_t)b * T + par) * p.ld + x_own];
     }
 
-    // ---- row maxima and masses: four threads per row merge its chunks, sixteen chunks per thread
-    // requested at a time (one memory round trip for vocabularies up to 64 chunks), merged online
+    // ---- row maxima and masses, merged online. When all rows' chunk statistics fit (T * chunks
+    // <= kKeepStats) they also stay in LDS, so that the per-chunk masses a rejection or the bonus
+    // draw needs later cost no second trip to memory.
+    const bool keep = T * p.chunks <= kKeepStats;
     {
-        constexpr int kPre = 16;
-        const int i = tid >> 2, sub = tid & 3;
-        const int64_t row = (int64_t)b * T + i;
         float m = -INFINITY, z = 0.f;
         for (int c0 = sub; c0 < p.chunks; c0 += 4 * kPre) {
-            float pm[kPre], ps[kPre];
+            if (c0 != sub) fetch_stats(c0);
+            if (keep) {
 #pragma unroll
-            for (int q = 0; q < kPre; ++q) {
-                const int c = c0 + 4 * q;
-                const bool ok = i < T && c < p.chunks;
-                pm[q] = ok ? p.part_m[row * p.chunks + c] : -INFINITY;
-                ps[q] = ok ? p.part_s[row * p.chunks + c] : 0.f;
+                for (int q = 0; q < kPre; ++q) {
+                    const int c = c0 + 4 * q;
+                    if (ri < T && c < p.chunks) {
+                        skeep_m[ri * p.chunks + c] = pm[q];
+                        skeep_s[ri * p.chunks + c] = ps[q];
+                    }
+                }
             }
             float bm = m;
 #pragma unroll
@@ -146,13 +171,13 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
         if (m > -INFINITY) z *= __builtin_amdgcn_exp2f((m - mm) * p.k_log2);
         z += __shfl_xor(z, 1);
         z += __shfl_xor(z, 2);
-        if (i < T && sub == 0) {
-            sM[i] = mm;
-            sZ[i] = z;
+        if (ri < T && sub == 0) {
+            sM[ri] = mm;
+            sZ[ri] = z;
         }
     }
     if (tid < T) {
-        su[tid] = p.u_accept[(int64_t)b * T + tid];
+        su[tid] = u_own;
         sdraft[tid] = x_own;
     }
     __syncthreads();
@@ -238,15 +263,25 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
         const float M = sM[node];
         __syncthreads();
         for (int c = tid; c < p.chunks; c += kWalkThreads) {
-            const float mc = p.part_m[row * p.chunks + c];
-            sch[c] = (mc > -INFINITY) ? p.part_s[row * p.chunks + c] * __builtin_amdgcn_exp2f((mc - M) * p.k_log2) : 0.f;
+            const float mc = keep ? skeep_m[node * p.chunks + c] : p.part_m[row * p.chunks + c];
+            const float sc = keep ? skeep_s[node * p.chunks + c] : p.part_s[row * p.chunks + c];
+            sch[c] = (mc > -INFINITY) ? sc * __builtin_amdgcn_exp2f((mc - M) * p.k_log2) : 0.f;
         }
         __syncthreads();
         for (int r = 0; r < nrem; ++r) remove_from_chunks(node, r);
         return chunk_total();
     };
 
-    // ---- the walk
+    // ---- the walk. Every wave runs it on registers: lane c holds node c's parent, draft token,
+    // weight and uniform (T <= 64), the children of the current node are a ballot, and a child's
+    // values are read with v_readlane - no LDS access and no dependent address per candidate
+    // (a scan over LDS copies cost ~100 clocks per tree node and step). The removed tokens of
+    // the current node sit one per lane for the duplicate check; LDS keeps the copy that the
+    // chunk-wide passes read.
+    const int32_t par_c = (lane < T) ? sp[lane] : -2;
+    const int32_t x_c = (lane < T) ? sdraft[lane] : -1;
+    const float ex_c = (lane >= 1 && lane < T) ? sex[lane] : 0.f;
+    const float u_c = (lane < T) ? su[lane] : 2.f;
     int cur = 0, alen = 0, nrem = 0;
     float Z = 0.f;
     bool have_chunks = false;
@@ -254,15 +289,19 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
         Z = sZ[cur];
         nrem = 0;
         have_chunks = false;
+        int32_t rem_x = 0; // lane r < nrem: the r-th removed token
         int next = -1;
-        for (int c = cur + 1; c < T && next < 0; ++c) {
-            if (sp[c] != cur) continue;
-            const int32_t x = sdraft[c];
+        uint64_t kids = __ballot(par_c == cur); // children in increasing node order
+        while (kids != 0 && next < 0) {
+            const int c = __builtin_ctzll(kids);
+            kids &= kids - 1;
+            const int32_t x = __builtin_amdgcn_readlane(x_c, c);
             bool gone = x < 0 || x >= p.V;
-            for (int r = 0; r < nrem; ++r) gone = gone || sremoved[r] == x;
-            const float ex = gone ? 0.f : sex[c];
+            gone = gone || __ballot(lane < nrem && rem_x == x) != 0;
+            const float ex = gone ? 0.f : __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, ex_c), c));
+            const float u = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, u_c), c));
             const float prob = (Z > 0.f) ? ex / Z : 0.f;
-            if (su[c] < prob) {
+            if (u < prob) {
                 next = c;
             } else if (!gone) {
                 __syncthreads(); // every thread has read the list
@@ -270,6 +309,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
                     sremoved[nrem] = x;
                     sremoved_ex[nrem] = ex;
                 }
+                if (lane == nrem) rem_x = x;
                 ++nrem;
                 __syncthreads();
                 if (have_chunks) {
@@ -338,20 +378,27 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
 #pragma unroll
         for (int e = 0; e < kPerThread; ++e)
             if (w[e] > 0.f) last = j0 + e;
-        if (last >= 0) atomicMax(&slast, last);
+        // one LDS atomic per wave, not per thread (256 atomics on one address take microseconds)
+        int wlast = last;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) wlast = max(wlast, __shfl_xor(wlast, o));
+        if (lane == 0 && wlast >= 0) atomicMax(&slast, wlast);
+        int cand = INT32_MAX;
         if (inc > local && last >= 0) {
             // first element of this thread whose running sum passes the target; the scan's and
             // the running sum's roundings may disagree by an ulp, then the last weighted one
             float acc = inc - s;
-            int cand = -1;
+            cand = -1;
 #pragma unroll
             for (int e = 0; e < kPerThread; ++e) {
                 acc += w[e];
                 if (cand < 0 && acc > local && w[e] > 0.f) cand = j0 + e;
             }
             if (cand < 0) cand = last;
-            atomicMin(&spick, cand);
         }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) cand = min(cand, __shfl_xor(cand, o));
+        if (lane == 0 && cand != INT32_MAX) atomicMin(&spick, cand);
     }
     __syncthreads();
     // ---- results
