@@ -250,6 +250,9 @@ __global__ __launch_bounds__(kExpandThreads) void draft_expand_select_kernel(con
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int F = p.F, K = p.K, C = F * K;
     const int keep = min(K, C);
+    // candidate tid's parent (the frontier row it extends): requested now, written out at the end
+    // (C <= kMaxDraftCand = the block size, so a thread owns at most one candidate)
+    const int32_t par_own = (tid < C && p.frontier_cand) ? p.frontier_cand[(int64_t)b * F + tid / K] : -1;
 
     // ---- per row: log-sum-exp and the K first entries of the merged chunk lists
     for (int f = wave; f < F; f += kExpandThreads / kWave) {
@@ -311,6 +314,31 @@ __global__ __launch_bounds__(kExpandThreads) void draft_expand_select_kernel(con
     __syncthreads();
 
     // ---- next frontier: the `keep` first candidates in (score descending, index ascending), by counting
+    if (C <= kWave) {
+        // one wave, registers only: lane c holds candidate c, the others' scores come by v_readlane,
+        // the position among the kept ones is a population count of a ballot
+        if (wave != 0) return;
+        const float sc = (lane < C) ? s_score[lane] : -INFINITY;
+        int rank = 0;
+        for (int o = 0; o < C; ++o) {
+            const float so = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int32_t, sc), o));
+            rank += before(so, o, sc, lane) ? 1 : 0;
+        }
+        const bool kept = lane < C && rank < keep;
+        const uint64_t kept_mask = __ballot(kept);
+        if (lane < C) {
+            const int64_t g = (int64_t)b * p.cand_capacity + p.cand_base + lane;
+            p.cand_token[g] = s_token[lane];
+            p.cand_score[g] = sc;
+            p.cand_parent[g] = par_own;
+            const int pos = __builtin_popcountll(kept_mask & ((1ull << lane) - 1ull));
+            if (kept && pos < keep) { // pos >= keep: only NaN scores can rank more than `keep` candidates first
+                p.next_frontier_cand[(int64_t)b * keep + pos] = p.cand_base + lane;
+                p.next_cum[(int64_t)b * keep + pos] = sc;
+            }
+        }
+        return;
+    }
     for (int c = tid; c < C; c += kExpandThreads) {
         const float sc = s_score[c];
         int rank = 0;
@@ -322,7 +350,7 @@ __global__ __launch_bounds__(kExpandThreads) void draft_expand_select_kernel(con
         const int64_t g = (int64_t)b * p.cand_capacity + p.cand_base + c;
         p.cand_token[g] = s_token[c];
         p.cand_score[g] = s_score[c];
-        p.cand_parent[g] = p.frontier_cand ? p.frontier_cand[(int64_t)b * F + c / K] : -1;
+        p.cand_parent[g] = par_own;
         if (s_keep[c]) {
             int pos = 0;
             for (int o = 0; o < c; ++o) pos += s_keep[o];
@@ -335,19 +363,23 @@ __global__ __launch_bounds__(kExpandThreads) void draft_expand_select_kernel(con
 
 // grid = B, block = 256.
 __global__ __launch_bounds__(kSelThreads) void draft_tree_build_kernel(const DraftBuildParams p) {
-    __shared__ float s_score[kMaxDraftTotal];
+    constexpr int kWords = kMaxDraftTotal / 64;
+    __shared__ __attribute__((aligned(16))) float s_score[kMaxDraftTotal + 4];
     __shared__ int32_t s_parent[kMaxDraftTotal];
-    __shared__ uint8_t s_pick[kMaxDraftTotal];
+    __shared__ uint64_t s_mask[kWords];   // picked candidates, one bit each
+    __shared__ int32_t s_before[kWords];  // picked candidates below word w
     __shared__ int32_t s_bad;
     const int b = blockIdx.x;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int M = p.M, N = p.N;
     const int take = min(N, M);
     const int32_t* tok = p.cand_token + (int64_t)b * p.cand_capacity;
     const float* score = p.cand_score + (int64_t)b * p.cand_capacity;
     const int32_t* par = p.cand_parent + (int64_t)b * p.cand_capacity;
+    const int rounds = (M + kSelThreads - 1) / kSelThreads; // every thread runs all rounds: the ballots need whole waves
     if (tid == 0) s_bad = 0;
     __syncthreads();
+    if (tid < ((M + 3) & ~3) - M) s_score[M + tid] = -INFINITY; // padding of the last group of four
     for (int c = tid; c < M; c += kSelThreads) {
         s_score[c] = score[c];
         const int32_t pc = par[c];
@@ -355,16 +387,38 @@ __global__ __launch_bounds__(kSelThreads) void draft_tree_build_kernel(const Dra
         if (pc < -1 || pc >= c) atomicOr(&s_bad, 1);
     }
     __syncthreads();
-    for (int c = tid; c < M; c += kSelThreads) {
-        const float sc = s_score[c];
-        int rank = 0;
-        for (int o = 0; o < M; ++o) rank += before(s_score[o], o, sc, c) ? 1 : 0;
-        s_pick[c] = rank < take ? 1 : 0;
+    // rank by counting (four scores per LDS read; a padding entry is -inf at an index >= M > c,
+    // which comes before nothing), picked = rank < take, one bit per candidate
+    const int M4 = (M + 3) & ~3;
+    for (int r = 0; r < rounds; ++r) {
+        const int c = r * kSelThreads + tid;
+        bool pick = false;
+        if (c < M) {
+            const float sc = s_score[c];
+            int rank = 0;
+            for (int o = 0; o < M4; o += 4) {
+                const f32x4 so = *(const f32x4*)&s_score[o];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rank += before(so[e], o + e, sc, c) ? 1 : 0;
+            }
+            pick = rank < take;
+        }
+        const uint64_t m = __ballot(pick);
+        if (lane == 0) s_mask[c >> 6] = m;
     }
     __syncthreads();
+    const int words = (M + 63) >> 6;
+    if (tid == 0) {
+        int acc = 0;
+        for (int w = 0; w < words; ++w) {
+            s_before[w] = acc;
+            acc += __builtin_popcountll(s_mask[w]);
+        }
+    }
+    auto picked = [&](int c) { return (s_mask[c >> 6] >> (c & 63)) & 1ull; };
     if (!s_bad) {
         for (int c = tid; c < M; c += kSelThreads)
-            if (s_pick[c] && s_parent[c] >= 0 && !s_pick[s_parent[c]]) atomicOr(&s_bad, 1);
+            if (picked(c) && s_parent[c] >= 0 && !picked(s_parent[c])) atomicOr(&s_bad, 1);
     }
     __syncthreads();
     const bool bad = s_bad != 0;
@@ -382,18 +436,14 @@ __global__ __launch_bounds__(kSelThreads) void draft_tree_build_kernel(const Dra
         if (p.status) p.status[b] = bad ? VS_STATUS_BAD_CANDIDATE : VS_STATUS_OK;
     }
     if (bad) return;
+    // node id = 1 + number of picked candidates with a smaller index
+    auto node_of = [&](int c) { return 1 + s_before[c >> 6] + __builtin_popcountll(s_mask[c >> 6] & ((1ull << (c & 63)) - 1ull)); };
     for (int c = tid; c < M; c += kSelThreads) {
-        if (!s_pick[c]) continue;
-        int node = 1;
-        for (int o = 0; o < c; ++o) node += s_pick[o];
+        if (!picked(c)) continue;
+        const int node = node_of(c);
         if (node > take) continue; // only NaN scores can rank more than `take` candidates first
         const int32_t pc = s_parent[c];
-        int pnode = 0;
-        if (pc >= 0) {
-            pnode = 1;
-            for (int o = 0; o < pc; ++o) pnode += s_pick[o];
-        }
-        o_parent[node] = pnode;
+        o_parent[node] = pc >= 0 ? node_of(pc) : 0;
         o_tokens[node] = tok[c];
         o_cand[node] = c;
     }
