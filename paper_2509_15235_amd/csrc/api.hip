@@ -99,16 +99,25 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     const bool big = units0 >= 48;
     int rpw = d->rows_per_wave, waves = d->waves_per_group, splits = d->num_splits;
     const bool pipe_ok = (rpw == 0 || rpw == 1) && (waves == 0 || waves == 4 || waves == 8);
+    const bool many = units0 >= 12; // enough (sequence, KV head) units for the pipelined kernel, see below
     // few units, several row blocks, a short sequence (at most 2048 keys) and no caller's
     // choice that it cannot honour: the LDS-resident kernel, whose second split of the keys
     // among the waves shortens each workgroup's loop. Measured on C3-sized layers replayed from
     // a HIP graph over 400 MB of K/V (every layer cold in the caches): 19.0 us per layer with
     // 10 splits, the streaming loop 19.2 us; slower than the loop for two row blocks and for
     // 5000+ keys, where its 256-key limit forces too many partial results.
-    const bool resident_ok = !big && nrb >= 3 && tiles <= 32 && (rpw == 0 || rpw == 1) && (waves == 0 || waves == 8) &&
-                             (splits <= 0 || (tiles + splits - 1) / splits <= kResidentMaxKeys / kIterKeys);
+    // ... and only while all its workgroups (128 KB of LDS each: one per CU) run at once: with two
+    // sequences (320 workgroups) it already takes 30.7 us against the loop's 24.6, with eleven 85 against 51.
+    const int res_splits = splits > 0 ? splits : (tiles + 2) / 3;
+    const bool resident_ok = !many && nrb >= 3 && tiles <= 32 && (rpw == 0 || rpw == 1) && (waves == 0 || waves == 8) &&
+                             (splits <= 0 || (tiles + splits - 1) / splits <= kResidentMaxKeys / kIterKeys) &&
+                             (int64_t)units0 * ((nrb + 3) / 4) * res_splits <= 256;
+    // The pipelined kernel takes over from twelve units on (three C3 sequences, or one MHA
+    // layer): A/B per call, loop against pipelined, 3 sequences 26.3 / 24.9 us, 4: 28.6 / 26.9,
+    // 6: 34.0 / 29.7, 8: 39.9 / 31.4, 11: 50.9 / 39.9, one C2 (MHA) layer 25.4 / 23.3; below
+    // that the loop wins (one C3 sequence 19.1 / 22.5, two 21.7 / 23.3).
     pl.schedule = d->schedule != VS_SCHED_AUTO ? d->schedule
-                  : big && pipe_ok             ? VS_SCHED_PIPELINED
+                  : many && pipe_ok            ? VS_SCHED_PIPELINED
                   : resident_ok                ? VS_SCHED_RESIDENT
                                                : VS_SCHED_LOOP;
     if (pl.schedule == VS_SCHED_RESIDENT) {
@@ -178,14 +187,15 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
         // partial results at the end of the kernel (about 0.2 us per split for a C3-sized
         // launch) and the combine grow with the split count, the loop (about 2 us per 64 keys
         // with one wave per SIMD) with the keys per split; measured optima were 3 iterations
-        // of 64 keys per split for short sequences and 8 for long ones, with at most ~1.5
-        // workgroups per CU.
+        // of 64 keys per split for short sequences and 8 for long ones, with at most one
+        // workgroup per CU (two C3 sequences: 7 splits = 224 workgroups 21.7 us, 10 splits = 320
+        // workgroups 25.1 us).
         if (big) {
             splits = 256 / units;
         } else {
             const int iters = tiles <= 32 ? 3 : (tiles <= 64 ? 5 : 8);
             splits = (tiles + iters - 1) / iters;
-            const int cap = (384 + units / 2) / units;
+            const int cap = 256 / units; // one workgroup per CU: a second one on some CUs makes those the tail
             if (splits > cap) splits = cap;
         }
         const int max_splits = (tiles + 1) / 2;

@@ -99,11 +99,18 @@ def test_plan_and_workspace_sizes():
     assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
     assert vs.vs_attention_plan(_desc(waves_per_group=4))[1].schedule == vs.VS_SCHED_LOOP
     assert vs.vs_attention_plan(_desc(num_splits=2))[1].schedule == vs.VS_SCHED_LOOP
-    # ... and for long sequences or two row blocks (MHA)
+    # ... for more sequences than fit in one round of its workgroups (one per CU): two sequences
+    # take the loop with one workgroup per CU
+    rc, two = vs.vs_attention_plan(_desc(B=2))
+    assert two.schedule == vs.VS_SCHED_LOOP and two.num_splits == 7 and two.workgroups == 224
+    # ... and for long sequences
     one_long = _desc(max_prefix_len=6684, capacity=6800, stride_head=6800 * 128)
     assert vs.vs_attention_plan(one_long)[1].schedule == vs.VS_SCHED_LOOP
-    one_mha = _desc(Hq=32, Hkv=32, stride_seq=32 * 1800 * 128)
-    assert vs.vs_attention_plan(one_mha)[1].schedule == vs.VS_SCHED_LOOP
+    # from twelve (sequence, KV head) units on the pipelined kernel: three GQA sequences, one MHA layer
+    rc, three = vs.vs_attention_plan(_desc(B=3))
+    assert three.schedule == vs.VS_SCHED_PIPELINED and three.waves_per_group == 8 and three.workgroups <= 256
+    rc, one_mha = vs.vs_attention_plan(_desc(Hq=32, Hkv=32, stride_seq=32 * 1800 * 128))
+    assert one_mha.schedule == vs.VS_SCHED_PIPELINED and one_mha.waves_per_group == 4 and one_mha.workgroups <= 256
     # an explicit resident schedule caps a split at 256 keys whatever split count is asked for
     rc, pr = vs.vs_attention_plan(_desc(schedule=vs.VS_SCHED_RESIDENT, num_splits=1, max_prefix_len=6684, capacity=6800,
                                         stride_head=6800 * 128))
@@ -140,8 +147,11 @@ def test_plan_and_workspace_sizes():
     assert vs.vs_attention_plan(_desc(waves_per_group=3))[0] == -2
     rc, pg = vs.vs_attention_plan(_desc(dtype=vs.VS_F32))
     assert pg.impl == vs.VS_IMPL_GENERIC and vs.vs_attention_workspace_bytes(_desc(dtype=vs.VS_F32)) == 0
+    # MHA: two row blocks per unit; the loop uses two waves, the pipelined kernel four
+    rc, pm = vs.vs_attention_plan(_desc(Hq=32, Hkv=32, max_prefix_len=3136, capacity=3300, schedule=vs.VS_SCHED_LOOP))
+    assert pm.waves_per_group == 2 and pm.rows_per_wave == 1 and pm.num_splits > 1 and pm.workgroups <= 256
     rc, pm = vs.vs_attention_plan(_desc(Hq=32, Hkv=32, max_prefix_len=3136, capacity=3300))
-    assert pm.waves_per_group == 2 and pm.rows_per_wave == 1 and pm.num_splits > 1
+    assert pm.schedule == vs.VS_SCHED_PIPELINED and pm.waves_per_group == 4 and pm.num_splits == 8 and pm.workgroups == 256
 
 
 def test_calls_reject_bad_arguments_before_any_launch():
