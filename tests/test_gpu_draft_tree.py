@@ -132,6 +132,32 @@ def test_build_on_handmade_candidates(gu, oracle_mod):
             _check_build(gu, oracle_mod, dd, N)
 
 
+@pytest.mark.parametrize("M,N", [(2048, 63), (2047, 40), (1025, 63), (257, 30), (66, 63), (65, 5)])
+def test_build_at_large_candidate_counts(gu, oracle_mod, M, N):
+    """Up to the maximum the build accepts: random forests whose scores fall along every parent
+    chain (as cumulative log-probabilities do), with many exactly equal scores, at counts that are
+    not multiples of the kernel's group sizes (4 scores per read, 64 candidates per ballot, 256 per
+    round)."""
+    import torch
+    r = np.random.default_rng(M * 131 + N)
+    B = 2
+    tok = r.integers(0, 50000, size=(B, M)).astype(np.int32)
+    par = np.empty((B, M), np.int32)
+    sc = np.empty((B, M), np.float32)
+    for b in range(B):
+        for c in range(M):
+            pc = -1 if (c == 0 or r.random() < 0.02) else int(r.integers(max(0, c - 300), c))
+            par[b, c] = pc
+            base = 0.0 if pc < 0 else float(sc[b, pc])
+            sc[b, c] = np.float32(base - float(r.choice([0.0, 0.25, 0.5, 1.0, 3.0])))   # ties, also with the parent
+    dd = gu.DeviceDraft(B, 16, M)
+    dd.tok[:] = torch.from_numpy(tok)
+    dd.score[:] = torch.from_numpy(sc)
+    dd.par[:] = torch.from_numpy(par)
+    dd.M = M
+    _check_build(gu, oracle_mod, dd, N)
+
+
 def test_build_reports_malformed_candidates(gu, oracle_mod):
     import torch
     dd = gu.DeviceDraft(4, 2, 3)
