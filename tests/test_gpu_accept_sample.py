@@ -78,6 +78,14 @@ def test_matches_oracle_qwen_vocab(gu, oracle_mod):
     assert alen.max() >= 1
 
 
+@pytest.mark.parametrize("T,V", [(8, 300000), (64, 270001)])
+def test_matches_oracle_huge_vocab(gu, oracle_mod, T, V):
+    """More than 64 chunks per row (a second batch of chunk statistics per thread), and - with 64
+    nodes - more chunk statistics than the walk kernel keeps in LDS (it reads them from memory again)."""
+    parent, tokens, logits, ua, ub = _case(200 + T, 2, T, V)
+    _check(gu, oracle_mod, logits, tokens, parent, 1.0, ua, ub, min_exact_frac=0.5)
+
+
 def test_single_node_tree_is_plain_sampling(gu, oracle_mod):
     parent, tokens, logits, ua, ub = _case(5, 16, 1, 5000)
     alen, path, _, _ = _check(gu, oracle_mod, logits, tokens, parent, 1.0, ua, ub)

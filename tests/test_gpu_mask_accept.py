@@ -71,6 +71,14 @@ def test_accept_configs(gu, oracle_mod, name):
     assert alen.shape == (cfg.B,)
 
 
+def test_accept_huge_vocab(gu, oracle_mod):
+    """More than 64 chunks per row: the walk kernel fetches a second batch of chunk results."""
+    import dataclasses
+    cfg = dataclasses.replace(gen.CONFIGS["C1"], V=300001, T=9, B=2, max_depth=4, prefix=[4, 4])
+    ai = gen.accept_inputs(cfg, 321)
+    _check_accept(gu, oracle_mod, ai.logits, ai.tokens, ai.parent)
+
+
 def test_accept_ragged_batch_shape(gu, oracle_mod):
     # C5's acceptance: 16 independent trees; vocab cut to keep the host copy small
     cfg = gen.CONFIGS["C5"]
