@@ -94,6 +94,14 @@ def test_shapes(gu, oracle_mod, V, K, D, N):
     _check_build(gu, oracle_mod, dd, N)
 
 
+@pytest.mark.parametrize("V,K", [(152064, 16), (300000, 8), (270001, 16)])
+def test_long_rows(gu, oracle_mod, V, K):
+    """Rows whose merged chunk lists do not fit a wave's registers (chunks x K > 512: the lists are
+    re-read per extracted entry) and rows of more than 64 chunks (chunk statistics in several passes)."""
+    dd = _grow_both(gu, oracle_mod, 40 + K, 2, V, K, 2)
+    _check_build(gu, oracle_mod, dd, 30)
+
+
 def test_equal_logits_take_the_lower_token_id(gu, oracle_mod):
     def plateau(level, logits):
         logits[:, :, ::5] = np.float32(20.0)                            # many equal maxima, across chunks too
