@@ -31,6 +31,8 @@ def gu():
 
 def _check(gu, oracle_mod, logits, tokens, parent, temperature, ua, ub, min_exact_frac=0.9, **kw):
     alen, path, bonus, status = gu.run_accept_sample(logits, tokens, parent, temperature, ua, ub, **kw)
+    again = gu.run_accept_sample(logits, tokens, parent, temperature, ua, ub, **kw)     # nothing may depend on timing
+    assert (again[0] == alen).all() and (again[1] == path).all() and (again[2] == bonus).all()
     ua64, ub64 = ua.astype(np.float64), ub.astype(np.float64)
     o_alen, o_path, o_bonus, margin = oracle_mod.tree_accept_sample(logits, tokens, parent, temperature, ua64, ub64)
     assert (status == 0).all()

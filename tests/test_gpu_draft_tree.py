@@ -64,6 +64,8 @@ def _grow_both(gu, oracle_mod, seed, B, V, K, D, mutate=None, **kw):
 
 def _check_build(gu, oracle_mod, dd, N, root_token=None):
     parent, tokens, node_cand, num, status = dd.build(N, root_token)
+    again = dd.build(N, root_token)                                                     # nothing may depend on timing
+    assert all((a == b).all() for a, b in zip(again, (parent, tokens, node_cand, num, status)))
     tok, sc, par = dd.tok.cpu().numpy(), dd.score.cpu().numpy(), dd.par.cpu().numpy()
     for b in range(dd.B):
         rc, o_parent, o_tokens, o_cand = oracle_mod.draft_tree_build_seq(
