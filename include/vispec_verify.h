@@ -18,7 +18,7 @@
  *   vs_draft_tree_build       expansion scored by cumulative log-probability, best-N selection
  *                             (Section 3.1's dynamic draft tree, Appendix A's parameters)
  *   vs_compress_attention     the vision adaptor's attention: a few learnable queries over the
- *                             image embeddings (Section 3.2)
+ *                             image embeddings (Section 4.1, Fig. 3)
  *   vs_tree_kv_commit         keeps the accepted path's K/V rows, in order, behind the
  *                             prefix of the pre-allocated cache (Section 3.1, Appendix A)
  *
@@ -200,10 +200,10 @@ int32_t vs_tree_verify_attention(const vs_attn_desc* desc, const void* q, const 
                                  void* stream);
 
 /*
- * Compression attention of the vision adaptor (Section 3.2: a fixed set of learnable query
- * vectors attends to the image's visual features, which serve as keys and values, condensing
- * them into a few compressed image tokens; Eq. 1 with the softmax scale). Every query sees
- * every image embedding and nothing else. The adaptor's projections and the rest of its
+ * Compression attention of the vision adaptor (Section 4.1, Fig. 3: the adaptor owns a small,
+ * fixed number of trained query vectors; the image's visual features are the keys and the values
+ * of its attention, whose outputs are the few compressed image tokens the draft model reads;
+ * Eq. 1 with the softmax scale). Every query sees every image embedding and nothing else. The adaptor's projections and the rest of its
  * encoder layer are outside this library: q, k, v arrive projected.
  * The descriptor is read as for vs_tree_verify_attention with these meanings: T = number of
  * learnable queries (1..64; the paper studies 1 to 64), max_prefix_len = the largest kv_len

@@ -21,10 +21,24 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 OK, BAD_ROOT, BAD_PARENT, BAD_SIZE, BAD_PATH = 0, 1, 2, 3, 4
 
 
+# ORACLE_SANITIZE=1 selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer (any finding aborts). Python itself is not instrumented, so the
+# sanitizer runtime has to be preloaded:
+#   ORACLE_SANITIZE=1 ASAN_OPTIONS=detect_leaks=0 LD_PRELOAD=$(gcc -print-file-name=libasan.so) \
+#       python -m pytest tests -m "not gpu"
+_SANITIZE = os.environ.get("ORACLE_SANITIZE", "") not in ("", "0")
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "liboracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile oracle.c with gcc into liboracle.so next to it."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off",
+        flags = ["-O2"]
+        if _SANITIZE:
+            flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                     "-fno-sanitize-recover=all"]
+        subprocess.check_call(["gcc", *flags, "-std=c11", "-fPIC", "-shared", "-ffp-contract=off",
                                "-o", _LIB, _SRC, "-lm"])
     return _LIB
 

@@ -537,9 +537,9 @@ int oracle_draft_tree_build(const int32_t* cand_token, const float* cand_score, 
     return rc;
 }
 
-/* Compression attention of the vision adaptor (Section 3.2 "a lightweight vision adaptor":
- * a fixed set of learnable query vectors attends to the image's visual features, which serve
- * as keys and values; every query sees every image embedding; Eq. 1 with a softmax scale).
+/* Compression attention of the vision adaptor (Section 4.1, Fig. 3: a small fixed number of
+ * trained query vectors cross-attend to the image's visual features, the keys and values;
+ * every query sees every image embedding; Eq. 1 with a softmax scale).
  * The projections and the rest of the adaptor's encoder layer are outside this path: q, K, V
  * arrive already projected.
  *

@@ -5,7 +5,9 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libvispec_verify.so")
+# VISPEC_VERIFY_LIB names another build of the same library (e.g. the one whose host code is
+# compiled with sanitizers, see build.py)
+_LIB_PATH = os.environ.get("VISPEC_VERIFY_LIB") or os.path.join(_HERE, "libvispec_verify.so")
 
 VS_BF16, VS_F32 = 0, 1
 VS_IMPL_AUTO, VS_IMPL_GENERIC, VS_IMPL_MFMA = 0, 1, 2

@@ -18,11 +18,24 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
-def build_library(verbose: bool = False, extra=()) -> str:
-    """Compile every HIP source into one shared library. Always recompiles."""
+# host code under AddressSanitizer and UndefinedBehaviorSanitizer (device code is untouched)
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-sanitize-recover=all", "-g"]
+SAN_LIB = os.path.join(HERE, "libvispec_verify_san.so")
+
+
+def build_library(verbose: bool = False, extra=(), sanitize_host: bool = False) -> str:
+    """Compile every HIP source into one shared library. Always recompiles.
+    sanitize_host: build libvispec_verify_san.so instead, its host code instrumented; run it with
+    the compiler's own sanitizer runtime preloaded (Python is not instrumented):
+        RT=$(/opt/rocm/lib/llvm/bin/clang -print-file-name=libclang_rt.asan-x86_64.so)
+        VISPEC_VERIFY_LIB=$PWD/paper_2509_15235_amd/libvispec_verify_san.so ASAN_OPTIONS=detect_leaks=0 \
+        LD_PRELOAD=$RT LD_LIBRARY_PATH=$(dirname $RT) python -m pytest tests/test_boundary.py"""
     objs = []
     procs = []
-    bdir = os.path.join(HERE, "_build")
+    bdir = os.path.join(HERE, "_build_san" if sanitize_host else "_build")
+    if sanitize_host:
+        extra = list(extra) + SAN_FLAGS
     os.makedirs(bdir, exist_ok=True)
     for src in SOURCES:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
@@ -43,10 +56,13 @@ def build_library(verbose: bool = False, extra=()) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    out = SAN_LIB if sanitize_host else LIB
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs
+    if sanitize_host:
+        cmd += ["-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize", "-shared-libsan"]
     subprocess.check_call(cmd)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=True, sanitize_host="--sanitize-host" in sys.argv))

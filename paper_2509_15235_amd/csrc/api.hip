@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "vs_internal.h"
 
 namespace {
@@ -13,6 +15,30 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Is the current device one this library's kernels were written for? Asked once per device
+// and remembered; called after the argument checks and before the first enqueue.
+int32_t check_device() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> known[kMaxDevices]; // 0 = not asked yet, 1 = gfx950, -1 = something else
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
+        (void)hipGetLastError();
+        return VS_ERR_NO_DEVICE;
+    }
+    if (dev < kMaxDevices) {
+        const int k = known[dev].load(std::memory_order_relaxed);
+        if (k != 0) return k > 0 ? VS_OK : VS_ERR_NO_DEVICE;
+    }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return VS_ERR_NO_DEVICE;
+    }
+    const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+    if (dev < kMaxDevices) known[dev].store(ok ? 1 : -1, std::memory_order_relaxed);
+    return ok ? VS_OK : VS_ERR_NO_DEVICE;
+}
 
 struct Plan {
     int32_t impl, rpw, waves, row_groups, rows, rows_pad, num_splits, keys_per_split, total_wgs, schedule;
@@ -25,6 +51,7 @@ int32_t check_desc(const vs_attn_desc* d, int tree = 1) {
     if (d->B < 1 || d->T < 1 || d->T > VS_MAX_TREE || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0)
         return VS_ERR_SHAPE;
     if (d->d != 64 && d->d != 128) return VS_ERR_SHAPE;
+    if ((int64_t)d->B * d->Hkv > kMaxGridY) return VS_ERR_SHAPE; // one grid row per (sequence, KV head) in the combine
     if (d->max_prefix_len < 0) return VS_ERR_SHAPE;
     if (!(d->softmax_scale > 0.f) || !isfinite(d->softmax_scale)) return VS_ERR_SHAPE;
     if (d->dtype != VS_BF16 && d->dtype != VS_F32) return VS_ERR_DTYPE;
@@ -94,9 +121,9 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     //    split over row groups of eight (or four) waves, and key splits only when units x
     //    row groups leave CUs empty. No partial results when that alone fills the machine.
     //  * a caller who fixes rows_per_wave = 2 or a wave count the pipelined kernel does not
-    //    have gets the straight loop; with two row blocks per wave a small cost model in
-    //    microseconds still chooses the key splits.
-    const bool big = units0 >= 48;
+    //    have gets the straight loop: one row block per wave unless told otherwise, up to four
+    //    waves for small launches and eight for large ones.
+    const bool big = units0 >= kManyUnits;
     int rpw = d->rows_per_wave, waves = d->waves_per_group, splits = d->num_splits;
     const bool pipe_ok = (rpw == 0 || rpw == 1) && (waves == 0 || waves == 4 || waves == 8);
     const bool many = units0 >= 12; // enough (sequence, KV head) units for the pipelined kernel, see below
@@ -111,7 +138,7 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     const int res_splits = splits > 0 ? splits : (tiles + 2) / 3;
     const bool resident_ok = !many && nrb >= 3 && tiles <= 32 && (rpw == 0 || rpw == 1) && (waves == 0 || waves == 8) &&
                              (splits <= 0 || (tiles + splits - 1) / splits <= kResidentMaxKeys / kIterKeys) &&
-                             (int64_t)units0 * ((nrb + 3) / 4) * res_splits <= 256;
+                             (int64_t)units0 * ((nrb + 3) / 4) * res_splits <= kNumCUs;
     // The pipelined kernel takes over from twelve units on (three C3 sequences, or one MHA
     // layer): A/B per call, loop against pipelined, 3 sequences 26.3 / 24.9 us, 4: 28.6 / 26.9,
     // 6: 34.0 / 29.7, 8: 39.9 / 31.4, 11: 50.9 / 39.9, one C2 (MHA) layer 25.4 / 23.3; below
@@ -142,40 +169,18 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
         if (!waves) waves = nrb > 4 ? 8 : 4;
         if (splits <= 0) {
             const int wgs = units0 * ((nrb + waves - 1) / waves);
-            splits = wgs >= 200 ? 1 : 256 / wgs;
+            splits = wgs >= 200 ? 1 : kNumCUs / wgs;
             const int max_splits = (tiles + 3) / 4; // at least four iterations per split
             if (splits > max_splits) splits = max_splits;
         }
-    } else if (!big || nrb <= 4) {
+    } else {
         if (!rpw) rpw = 1;
         if (!waves) {
             const int need1 = (nrb + rpw - 1) / rpw;
+            const int cap = (big && nrb > 4) ? kMaxWaves : 4;
             waves = 1;
-            while (waves < need1 && waves < 4) waves *= 2;
+            while (waves < need1 && waves < cap) waves *= 2;
         }
-    } else if (!rpw) {
-        auto cost = [&](int r, int* out_splits) {
-            const int cap_blocks = kMaxWaves * r;                       // row blocks per workgroup
-            const int rg = (nrb + cap_blocks - 1) / cap_blocks;
-            const int blocks = (nrb + rg - 1) / rg;                     // ... actually used
-            const int wgs = units0 * rg;
-            int sp = splits > 0 ? splits : (wgs >= 256 ? 1 : 256 / wgs);
-            if (sp > (tiles + 1) / 2) sp = (tiles + 1) / 2;
-            if (sp < 1) sp = 1;
-            const double per_tile = (r == 2 ? 2.2 * blocks / 14.0 : 1.3 * blocks / 7.0) * 2.0; // per 64 keys
-            const double rounds = (double)((wgs * sp + 255) / 256);
-            *out_splits = sp;
-            return rounds * per_tile * ((tiles + sp - 1) / sp) + (sp > 1 ? 16.0 : 4.0);
-        };
-        int s1 = 1, s2 = 1;
-        const double c1 = cost(1, &s1), c2 = nrb >= 2 ? cost(2, &s2) : 1e30;
-        rpw = c2 < c1 ? 2 : 1;
-        if (splits <= 0) splits = rpw == 2 ? s2 : s1;
-    }
-    if (!waves) {
-        const int need2 = (nrb + rpw - 1) / rpw;
-        waves = 1;
-        while (waves < need2 && waves < kMaxWaves) waves *= 2;
     }
     pl.rpw = rpw;
     pl.waves = waves;
@@ -191,11 +196,11 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
         // workgroup per CU (two C3 sequences: 7 splits = 224 workgroups 21.7 us, 10 splits = 320
         // workgroups 25.1 us).
         if (big) {
-            splits = 256 / units;
+            splits = kNumCUs / units;
         } else {
             const int iters = tiles <= 32 ? 3 : (tiles <= 64 ? 5 : 8);
             splits = (tiles + iters - 1) / iters;
-            const int cap = 256 / units; // one workgroup per CU: a second one on some CUs makes those the tail
+            const int cap = kNumCUs / units; // one workgroup per CU: a second one on some CUs makes those the tail
             if (splits > cap) splits = cap;
         }
         const int max_splits = (tiles + 1) / 2;
@@ -264,6 +269,7 @@ int32_t vs_tree_mask_build(const int32_t* parent, int32_t B, int32_t T, uint64_t
                            int32_t* status, void* stream) {
     if (!parent || !mask || !depth) return VS_ERR_NULL;
     if (B < 1 || T < 1 || T > VS_MAX_TREE) return VS_ERR_SHAPE;
+    if (const int32_t dc = check_device()) return dc;
     return launch_tree_mask(parent, B, T, mask, depth, status, (hipStream_t)stream) == hipSuccess ? VS_OK
                                                                                                     : VS_ERR_HIP;
 }
@@ -304,6 +310,7 @@ int32_t enqueue_attention(const vs_attn_desc* desc, int tree, const void* q, con
     const size_t need = workspace_bytes(desc, pl);
     if (need > 0 && (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))))
         return VS_ERR_WORKSPACE;
+    if (const int32_t dc = check_device()) return dc;
 
     AttnParams p{};
     p.q = q;
@@ -396,8 +403,10 @@ int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V, const 
                        size_t workspace_bytes_given, void* stream) {
     if (!logits || !draft_tokens || !parent || !accepted_len || !path || !bonus_token) return VS_ERR_NULL;
     if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1 || ld_logits < V) return VS_ERR_SHAPE;
+    if ((int64_t)B * T > kMaxGridY) return VS_ERR_SHAPE; // one grid row per logits row
     const size_t need = vs_accept_workspace_bytes(B, T, V);
     if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;
+    if (const int32_t dc = check_device()) return dc;
     AcceptParams p{};
     p.logits = logits;
     p.ld = ld_logits;
@@ -434,10 +443,11 @@ int32_t vs_tree_accept_sample(const float* logits, int64_t ld_logits, int32_t V,
     if (!logits || !draft_tokens || !parent || !u_accept || !u_bonus || !accepted_len || !path || !bonus_token)
         return VS_ERR_NULL;
     if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1 || ld_logits < V) return VS_ERR_SHAPE;
-    if (accept_chunks(V) > kMaxSampleChunks) return VS_ERR_SHAPE;
+    if (accept_chunks(V) > kMaxSampleChunks || (int64_t)B * T > kMaxGridY) return VS_ERR_SHAPE;
     if (!(temperature > 0.f) || !(temperature < INFINITY)) return VS_ERR_SHAPE;
     const size_t need = vs_accept_sample_workspace_bytes(B, T, V);
     if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;
+    if (const int32_t dc = check_device()) return dc;
     SampleParams p{};
     p.logits = logits;
     p.ld = ld_logits;
@@ -475,10 +485,11 @@ int32_t vs_draft_expand(const float* logits, int64_t ld_logits, int32_t V, const
                         void* stream) {
     if (!logits || !cand_token || !cand_score || !cand_parent || !next_frontier_cand || !next_cum) return VS_ERR_NULL;
     if (B < 1 || F < 1 || F > VS_MAX_TREE || K < 1 || K > kMaxDraftK || F * K > kMaxDraftCand) return VS_ERR_SHAPE;
-    if (V < K || ld_logits < V) return VS_ERR_SHAPE;
+    if (V < K || ld_logits < V || (int64_t)B * F > kMaxGridY) return VS_ERR_SHAPE;
     if (cand_base < 0 || cand_capacity < 1 || (int64_t)cand_base + (int64_t)F * K > cand_capacity) return VS_ERR_SHAPE;
     const size_t need = vs_draft_expand_workspace_bytes(B, F, V, K);
     if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;
+    if (const int32_t dc = check_device()) return dc;
     DraftExpandParams p{};
     p.logits = logits;
     p.ld = ld_logits;
@@ -517,6 +528,7 @@ int32_t vs_draft_tree_build(const int32_t* cand_token, const float* cand_score, 
     if (!cand_token || !cand_score || !cand_parent || !parent || !draft_tokens || !node_cand || !num_nodes)
         return VS_ERR_NULL;
     if (B < 1 || M < 1 || M > kMaxDraftTotal || cand_capacity < M || N < 1 || N > VS_MAX_TREE - 1) return VS_ERR_SHAPE;
+    if (const int32_t dc = check_device()) return dc;
     DraftBuildParams p{};
     p.cand_token = cand_token;
     p.cand_score = cand_score;
@@ -556,6 +568,8 @@ int32_t vs_tree_kv_commit(const vs_kv_desc* d, void* k_cache, void* v_cache, con
         return VS_ERR_LAYOUT;
     if (!aligned16(k_cache) || !aligned16(v_cache)) return VS_ERR_LAYOUT;
     if (new_prefix_len == prefix_len) return VS_ERR_LAYOUT;
+    if ((((int64_t)d->num_layers * 2 * d->Hkv * (d->d * eb / 16)) + 255) / 256 > 0x7fffffffLL || d->B > kMaxGridY) return VS_ERR_SHAPE;
+    if (const int32_t dc = check_device()) return dc;
     CommitParams p{};
     p.k = k_cache;
     p.v = v_cache;
@@ -582,7 +596,6 @@ int32_t vs_tree_kv_commit(const vs_kv_desc* d, void* k_cache, void* v_cache, con
     p.stride_block_bytes = d->stride_block * eb;
     p.stride_head_bytes = d->stride_head * eb;
     p.stride_tok_bytes = d->stride_tok * eb;
-    if ((p.items_per_seq + 255) / 256 > 0x7fffffffLL || d->B > 65535) return VS_ERR_SHAPE;
     return launch_kv_commit(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
 }
 

@@ -23,7 +23,7 @@
 //   is, after rounding to bf16, already a B operand; the V reads pick keys in that order)
 //
 // With one split the normalised result is written as bf16; otherwise partials (O divided
-// by the row's sum, as fp16; running max and sum as fp32) go to the workspace, laid out
+// by the row's sum, as bf16; running max and sum as fp32) go to the workspace, laid out
 // exactly as the accumulator registers are (so every store is contiguous per wave), and
 // the combine kernel merges them.
 #include <type_traits>

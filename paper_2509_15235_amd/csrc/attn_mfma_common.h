@@ -35,23 +35,25 @@ __device__ __forceinline__ float half_sum(float x) {
 }
 
 // Partial results of one (sequence, KV head, split, 32-row block): D/32 accumulator blocks,
-// each stored as 4 x [64 lanes x 4 halves] (register r = 4*q4 + e of lane l at
+// each stored as 4 x [64 lanes x 4 values] (register r = 4*q4 + e of lane l at
 // ((db*4 + q4)*64 + l)*4 + e), followed elsewhere by 32 x (max, sum) in fp32. A partial output
-// row is divided by its own sum before it is rounded to fp16: a convex combination of V rows,
-// so it cannot leave fp16's range, and its 2^-11 rounding stays well below the bf16 rounding
-// of the final result. Half the bytes of fp32 partials: what a split costs is mostly the
-// write-back of these bytes at the end of the kernel.
-typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
-typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+// row is divided by its own sum before it is rounded: a convex combination of V rows, as large
+// as the largest visible |V| and no larger. It is stored as bf16, which has V's own exponent
+// range (fp16 would turn any |v| > 65504 into infinity) and costs half the bytes of fp32: what a
+// split costs is mostly the write-back of these bytes at the end of the kernel. The 2^-9
+// rounding of each partial enters the merged row once (the merge weights sum to one), next to
+// the 2^-9 rounding of the final bf16 result.
 __device__ __forceinline__ u32x2 pack_partial(float a, float b, float c, float d, float inv) {
     const f32x2 lo = {a * inv, b * inv}, hi = {c * inv, d * inv};
     u32x2 w;
-    w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, f16x2));
-    w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, f16x2));
+    w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+    w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
     return w;
 }
 __device__ __forceinline__ f32x4 unpack_partial(u32x2 w) {
-    return __builtin_convertvector(__builtin_bit_cast(f16x4, w), f32x4);
+    const f32x4 r = {__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xffff0000u), __uint_as_float(w[1] << 16),
+                     __uint_as_float(w[1] & 0xffff0000u)};
+    return r;
 }
 __device__ __forceinline__ int64_t part_block(const AttnParams& p, int64_t unit, int split, int rbk) {
     return (unit * p.num_splits + split) * (int64_t)(p.rows_pad / kRowBlock) + rbk;

@@ -8,6 +8,15 @@
 
 namespace vs {
 
+// The machine this library is written for (MI355X, gfx950): what the launch planner and the
+// kernels' workgroup-id remap assume. api.hip checks the architecture of the current device
+// before the first launch on it (VS_ERR_NO_DEVICE otherwise).
+constexpr int kNumCUs = 256;            // compute units
+constexpr int kNumXCDs = 8;             // accelerator dies; consecutive workgroup ids go round-robin over them
+constexpr int kLdsBytesPerCU = 160 * 1024;
+constexpr int kMaxGridY = 65535;        // largest grid extent in y and z
+constexpr int kManyUnits = 48;          // (sequence, KV head) units from which the straight loop fills the CUs unaided
+
 constexpr int kWave = 64;
 constexpr int kTileKeys = 32;   // keys per MFMA score block of the attention kernel
 constexpr int kIterKeys = 64;   // keys staged in LDS per loop iteration (two score blocks)
@@ -27,7 +36,7 @@ struct AttnParams {
     const uint64_t* tree_mask;  // may be null
     const int32_t* block_table; // paged only
     int32_t* status;            // may be null
-    uint16_t* part_o;           // [unit][split][rows_pad][d] partial outputs, each row normalised by its own sum, fp16
+    uint16_t* part_o;           // [unit][split][rows_pad][d] partial outputs, each row normalised by its own sum, bf16
     float* part_ml;             // [unit][split][rows_pad][2] running max (log2 domain), sum
     int32_t B, T, Hq, Hkv, d, group;
     int32_t tree_keys;          // T when the queries' own K/V sit behind the prefix (verification), 0 when they

@@ -91,7 +91,7 @@ def test_plan_and_workspace_sizes():
     assert plan.keys_per_split == 192 and plan.num_splits == 10
     assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
     ws = vs.vs_attention_workspace_bytes(_desc())
-    assert ws >= 4 * plan.num_splits * 448 * (128 * 2 + 2 * 4)          # fp16 partial rows + fp32 (max, sum)
+    assert ws >= 4 * plan.num_splits * 448 * (128 * 2 + 2 * 4)          # bf16 partial rows + fp32 (max, sum)
     # ... the streaming loop when asked for, or when the caller's knobs rule the resident kernel out
     rc, plan = vs.vs_attention_plan(_desc(schedule=vs.VS_SCHED_LOOP))
     assert plan.schedule == vs.VS_SCHED_LOOP and plan.rows_per_wave == 1 and plan.waves_per_group == 4 and plan.row_groups == 4
@@ -173,6 +173,30 @@ def test_calls_reject_bad_arguments_before_any_launch():
     assert vs.vs_tree_accept(good, 9, 10, good, good, 1, 4, good, good, good, None, None, good, 1 << 20) == -2
     assert vs.vs_tree_accept(good, 10, 10, good, good, 1, 4, good, good, good, None, None, None, 0) == -4
     assert vs.vs_tree_accept(good, 10, 10, good, good, 1, 4, good, good, good, None, None, good, 8) == -4
+
+
+def test_sizes_beyond_a_grid_dimension_are_shape_errors():
+    """One grid row per logits row (or per sequence and KV head): more rows than a grid dimension
+    holds is reported as a shape error on the host, not left to the launch to refuse."""
+    g = 4096
+    big_b = 65535 // 60 + 1
+    assert vs.vs_tree_accept(g, 10, 10, g, g, big_b, 60, g, g, g, None, None, g, 1 << 30) == -2
+    assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, g, g, big_b, 60, g, g, g, None, g, 1 << 30) == -2
+    assert vs.vs_draft_expand(g, 100, 100, None, None, 65535 // 8 + 1, 8, 8, 0, 64, g, g, g, g, g, g, 1 << 30) == -2
+    assert vs.vs_attention_plan(_desc(B=65535 // 4 + 1))[0] == -2
+
+
+def test_no_device_is_reported_after_the_argument_checks():
+    """On a machine without a GPU a call whose arguments are all acceptable ends in VS_ERR_NO_DEVICE
+    before anything is enqueued (bad arguments still get their own codes, as above)."""
+    import torch
+    if torch.cuda.device_count() > 0:
+        pytest.skip("a GPU is visible")
+    g = 4096
+    assert vs.vs_tree_mask_build(g, 1, 4, g, g) == -7
+    assert vs.vs_tree_accept(g, 10, 10, g, g, 1, 4, g, g, g, None, None, g, 1 << 20) == -7
+    assert vs.vs_tree_verify_attention(_desc(num_splits=1), g, g, g, g, g, None, g) == -7
+    assert vs.vs_strerror(-7) == "no usable gfx950 device"
 
 
 def test_accept_sample_rejects_bad_arguments_before_any_launch():

@@ -7,9 +7,12 @@ the fp32 path's error of its threshold. Every GPU outcome must pass the oracle's
 comparison allowed to be off by EPS), and where the oracle's `margin` (the closest call of its
 own walk) exceeds EPS the outcome must equal the oracle's exactly. EPS bounds the fp32 error of
 a probability or of a normalised cumulative sum: hardware exp2 of an argument known to ~2e-6
-relative, sums of <= 2^23 terms in chunks of 4096 merged pairwise, ~5e-6 in all; 2e-5 is used.
-With a large vocabulary single tokens weigh less than EPS, so the bonus token may legitimately
-be a neighbour of the oracle's; the test also bounds how often that happens.
+relative, sums of <= 2^23 terms in chunks of 4096 merged pairwise, ~5e-6 in all; EPS is twice
+that. Every test prints the largest deviation any comparison actually needed (`worst`).
+With a large vocabulary single tokens weigh less than EPS (1 / 152064 = 6.6e-6), so the bonus
+token may legitimately be a neighbour of the oracle's: there the exact-match floor is the number
+of sequences whose margin exceeds EPS - which are checked one by one - and nothing more can be
+demanded.
 """
 import numpy as np
 import pytest
@@ -18,7 +21,7 @@ import gen
 
 pytestmark = pytest.mark.gpu
 
-EPS = 2e-5
+EPS = 1e-5
 
 
 @pytest.fixture(scope="module")
@@ -37,18 +40,20 @@ def _check(gu, oracle_mod, logits, tokens, parent, temperature, ua, ub, min_exac
     o_alen, o_path, o_bonus, margin = oracle_mod.tree_accept_sample(logits, tokens, parent, temperature, ua64, ub64)
     assert (status == 0).all()
     B, T, V = logits.shape
-    exact = 0
+    exact, clear, worst_all = 0, 0, 0.0
     for b in range(B):
         rc, worst = oracle_mod.tree_accept_sample_check_seq(logits[b], tokens[b], parent[b], temperature, ua64[b],
                                                             ub64[b], alen[b], path[b], bonus[b], EPS)
         assert rc == 0, (b, alen[b], path[b], bonus[b], o_alen[b], o_path[b], o_bonus[b], worst, margin[b])
+        worst_all = max(worst_all, float(worst))
         same = alen[b] == o_alen[b] and (path[b] == o_path[b]).all() and bonus[b] == o_bonus[b]
         if margin[b] > EPS:
+            clear += 1
             assert same, (b, alen[b], o_alen[b], bonus[b], o_bonus[b], margin[b])
-        else:
-            assert abs(int(alen[b]) - int(o_alen[b])) <= 1 or worst <= EPS
         exact += bool(same)
-    assert exact >= min_exact_frac * B - 1, f"only {exact} of {B} sequences equal the oracle's outcome"
+    print(f"accept_sample B={B} T={T} V={V} temperature={temperature}: worst deviation {worst_all:.3g} (EPS {EPS}), "
+          f"{exact} of {B} equal the oracle's outcome, {clear} have a margin above EPS")
+    assert exact >= max(clear, min_exact_frac * B - 1), f"only {exact} of {B} sequences equal the oracle's outcome"
     return alen, path, bonus, o_alen
 
 

@@ -207,6 +207,89 @@ def test_needles(gu, oracle_mod, impl, sched):
     gu.check_close(got[0, node, head], ref[0, node, head], 0.5, 1e-2, what="ancestor needle")
 
 
+def _scaled_values(cfg, seed, factor):
+    """Inputs whose V rows are N(0,1) times a power of two (exact in bf16), K and q unchanged."""
+    inp = gen.attention_inputs(cfg, seed)
+    inp.v_cache = (inp.v_cache.astype(np.float64) * factor).astype(np.float32)
+    inp.v_bits = gen.f32_to_bf16_bits(inp.v_cache)
+    assert np.array_equal(gen.bf16_bits_to_f32(inp.v_bits)[np.isfinite(inp.v_cache)], inp.v_cache[np.isfinite(inp.v_cache)])
+    return inp
+
+
+@pytest.mark.parametrize("exp2", [-20, 10, 17, 100])       # |V| around 1e-6, 1e3, 1.3e5 (beyond fp16's 65504), 1.3e30
+def test_value_range_on_every_split_schedule(gu, oracle_mod, exp2):
+    """bf16 values keep fp32's exponent range, and so must everything between the kernels: the
+    partial results of key splits travel through the workspace and may not narrow it. Every
+    schedule with more than one split, the in-kernel merge of key parts, and the unsplit forms."""
+    factor = 2.0 ** exp2
+    cfg = dataclasses.replace(gen.CONFIGS["C3"], B=2, prefix=[1100, 700])
+    inp = _scaled_values(cfg, 49, factor)
+    ref = oracle_mod.tree_attention(inp, threads=8)
+    assert np.isfinite(ref).all() and np.abs(ref).max() > 0.05 * factor
+    cases = [dict(schedule=vs.VS_SCHED_LOOP, num_splits=5), dict(schedule=vs.VS_SCHED_LOOP, num_splits=3, rows_per_wave=2, waves_per_group=8),
+             dict(schedule=vs.VS_SCHED_LOOP, num_splits=7, waves_per_group=1),
+             dict(schedule=vs.VS_SCHED_PIPELINED, num_splits=4, waves_per_group=8), dict(schedule=vs.VS_SCHED_PIPELINED, num_splits=2, waves_per_group=4),
+             dict(schedule=vs.VS_SCHED_RESIDENT), dict(schedule=vs.VS_SCHED_RESIDENT, num_splits=10 ** 6),
+             dict(), dict(num_splits=1), dict(schedule=vs.VS_SCHED_PIPELINED, num_splits=1), dict(impl=vs.VS_IMPL_GENERIC)]
+    for kw in cases:
+        da = gu.DeviceAttn(inp, **kw)
+        got = da.run()
+        assert (da.status.cpu().numpy() == 0).all()
+        if kw.get("num_splits", 0) not in (1,) and kw.get("impl") is None and kw:
+            assert da.plan().num_splits > 1, kw
+        gu.check_close(got, ref, CONTRACT[0] * factor, CONTRACT[1], what=f"contract, V x 2^{exp2}, {kw}")
+        gu.check_close(got, ref, TIGHT_LONG[0] * factor, TIGHT_LONG[1], what=f"tight, V x 2^{exp2}, {kw}")
+
+
+def test_channels_of_very_different_size_keep_their_relative_accuracy(gu, oracle_mod):
+    """One channel of V is 2^40 times larger than its neighbours: the small channels must still come
+    out to bf16 accuracy relative to their own size (a partial-result format with one exponent per
+    row would flush them)."""
+    cfg = dataclasses.replace(gen.CONFIGS["C3"], prefix=[900])
+    inp = gen.attention_inputs(cfg, 50)
+    scale_c = np.ones(cfg.d, dtype=np.float64)
+    scale_c[5::16] = 2.0 ** 40
+    inp.v_cache = (inp.v_cache.astype(np.float64) * scale_c).astype(np.float32)
+    inp.v_bits = gen.f32_to_bf16_bits(inp.v_cache)
+    ref = oracle_mod.tree_attention(inp, threads=8)
+    for kw in (dict(schedule=vs.VS_SCHED_RESIDENT), dict(schedule=vs.VS_SCHED_LOOP, num_splits=6),
+               dict(schedule=vs.VS_SCHED_PIPELINED, num_splits=3, waves_per_group=8)):
+        got = gu.DeviceAttn(inp, **kw).run()
+        err = np.abs(got - ref) / scale_c
+        bound = TIGHT_LONG[0] + TIGHT_LONG[1] * np.abs(ref) / scale_c
+        assert (err <= bound).all(), (kw, float((err - bound).max()))
+
+
+def test_non_finite_value_in_a_masked_tree_slot(gu, oracle_mod):
+    """Where the two sides differ by contract: K/V in every slot that is read must be finite. The
+    oracle skips a key a node may not see, so an Inf or NaN planted in a non-ancestor's V row leaves
+    that node's reference finite. The matrix-core kernels multiply such a row by a zero probability
+    instead (0 x Inf = NaN), so rows that mask the slot come out non-finite there, while rows whose
+    tile does not hold the slot, and the generic kernel (which skips like the oracle), stay exact."""
+    S, T = 300, 24
+    cfg = gen.Config("r19", 1, 7, 1, 128, T, 5, 3, 100, 0.5, 1, "bf16", prefix=[S])
+    inp = gen.attention_inputs(cfg, 51)
+    _, mask, _ = oracle_mod.tree_mask(inp.parent[0])
+    slot = T - 2
+    hides = [i for i in range(T) if not (int(mask[i]) >> slot & 1)]
+    sees = [i for i in range(T) if (int(mask[i]) >> slot & 1)]
+    assert hides and sees
+    inp.v_cache[0, 0, S + slot, 7] = np.inf
+    inp.v_bits = gen.f32_to_bf16_bits(inp.v_cache)
+    ref = oracle_mod.tree_attention(inp)
+    assert np.isfinite(ref[0, hides]).all() and not np.isfinite(ref[0, sees][..., 7]).any()
+    got = gu.DeviceAttn(inp, impl=vs.VS_IMPL_GENERIC).run()
+    gu.check_close(got[0, hides], ref[0, hides], *TIGHT_LONG, what="generic kernel skips masked keys")
+    assert not np.isfinite(got[0, sees][..., 7]).any()
+    for sched in (vs.VS_SCHED_LOOP, vs.VS_SCHED_PIPELINED, vs.VS_SCHED_RESIDENT):
+        got = gu.DeviceAttn(inp, impl=vs.VS_IMPL_MFMA, schedule=sched, num_splits=1).run()
+        assert not np.isfinite(got[0, sees][..., 7]).any()
+        # documented restriction: the masked rows' channel 7 is NaN here, every other channel is right
+        other = [c for c in range(cfg.d) if c != 7]
+        gu.check_close(got[0, hides][..., other], ref[0, hides][..., other], *TIGHT_LONG, what=f"other channels, schedule {sched}")
+        assert np.isnan(got[0, hides][..., 7]).all(), "the restriction documented for non-finite K/V no longer holds: compare with the oracle instead"
+
+
 def test_redundant_image_keys_closed_form(gu):
     """Paper Eq. 3-4 on the device: R identical keys + one unique key, T = 1."""
     import math

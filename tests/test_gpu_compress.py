@@ -85,7 +85,7 @@ def test_fp32_storage_and_head_dim_64(gu, oracle_mod):
 
 
 def test_redundant_image_embeddings(gu, oracle_mod):
-    """The situation Section 3.2 argues from: most image embeddings are copies of a few patterns.
+    """The situation Section 4.1 argues from: most image embeddings are copies of a few patterns.
     With R copies of one embedding and one unique embedding the queries' outputs follow Eq. 3."""
     nq, H, d, R = 4, 2, 128, 900
     inp = gen.compress_inputs(7, 1, nq, H, H, d, [R + 1])

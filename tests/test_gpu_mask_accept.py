@@ -63,12 +63,17 @@ def _check_accept(gu, oracle_mod, logits, tokens, parent, **kw):
     return alen
 
 
-@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
 def test_accept_configs(gu, oracle_mod, name):
+    """All five configurations at their stated sizes (C4: its own seed and planted-match
+    probability 0.6; C5: 16 independent trees over the full 152064-token vocabulary, 584 MB of logits)."""
     cfg = gen.CONFIGS[name]
     ai = gen.accept_inputs(cfg, 100 + int(name[1]))
+    assert ai.logits.shape == (cfg.B, cfg.T, cfg.V)
     alen = _check_accept(gu, oracle_mod, ai.logits, ai.tokens, ai.parent)
     assert alen.shape == (cfg.B,)
+    if cfg.B >= 8:
+        assert alen.max() >= 1 and len(set(alen.tolist())) > 1
 
 
 def test_accept_huge_vocab(gu, oracle_mod):
@@ -77,16 +82,6 @@ def test_accept_huge_vocab(gu, oracle_mod):
     cfg = dataclasses.replace(gen.CONFIGS["C1"], V=300001, T=9, B=2, max_depth=4, prefix=[4, 4])
     ai = gen.accept_inputs(cfg, 321)
     _check_accept(gu, oracle_mod, ai.logits, ai.tokens, ai.parent)
-
-
-def test_accept_ragged_batch_shape(gu, oracle_mod):
-    # C5's acceptance: 16 independent trees; vocab cut to keep the host copy small
-    cfg = gen.CONFIGS["C5"]
-    import dataclasses
-    cfg = dataclasses.replace(cfg, V=40000)
-    ai = gen.accept_inputs(cfg, 105)
-    alen = _check_accept(gu, oracle_mod, ai.logits, ai.tokens, ai.parent)
-    assert alen.max() >= 1
 
 
 @pytest.mark.parametrize("V,ld,off", [(1, 1, 0), (5, 5, 0), (1000, 1000, 0), (1000, 1003, 0), (1000, 1000, 1),
