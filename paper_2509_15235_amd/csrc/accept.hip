@@ -37,12 +37,13 @@ __device__ __forceinline__ Best wave_best(Best b) {
     return b;
 }
 
-// grid = (chunks, B*T), block = 256. Writes one (value, index) pair per (row, chunk).
+// grid = B*T*chunks, block = 256. Writes one (value, index) pair per (row, chunk).
 __global__ __launch_bounds__(kArgmaxBlock) void argmax_partial_kernel(const AcceptParams p) {
     __shared__ float sv[kArgmaxBlock / kWave];
     __shared__ int32_t si[kArgmaxBlock / kWave];
-    const int chunk = blockIdx.x;
-    const int64_t row = blockIdx.y;
+    // one-dimensional grid: workgroup id = row * chunks + chunk (the host keeps the product below 2^31)
+    const int64_t row = blockIdx.x / (uint32_t)p.chunks;
+    const int chunk = (int)(blockIdx.x - (uint32_t)row * (uint32_t)p.chunks);
     const float* __restrict__ lg = p.logits + row * p.ld;
     const int begin = chunk * p.chunk_elems;
     const int end = min(p.V, begin + p.chunk_elems);
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
 } // namespace
 
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s) {
-    hipLaunchKernelGGL(argmax_partial_kernel, dim3(p.chunks, p.B * p.T), dim3(kArgmaxBlock), 0, s, p);
+    hipLaunchKernelGGL(argmax_partial_kernel, dim3((unsigned)((int64_t)p.chunks * p.B * p.T)), dim3(kArgmaxBlock), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(accept_walk_kernel, dim3(p.B), dim3(256), 0, s, p);

@@ -40,8 +40,9 @@ __device__ __forceinline__ float wave_sum(float x) {
 __global__ __launch_bounds__(kArgmaxBlock) void softmax_stats_partial_kernel(const SampleParams p) {
     __shared__ float sm[kArgmaxBlock / kWave];
     __shared__ float ss[kArgmaxBlock / kWave];
-    const int chunk = blockIdx.x;
-    const int64_t row = blockIdx.y;
+    // one-dimensional grid: workgroup id = row * chunks + chunk (the host keeps the product below 2^31)
+    const int64_t row = blockIdx.x / (uint32_t)p.chunks;
+    const int chunk = (int)(blockIdx.x - (uint32_t)row * (uint32_t)p.chunks);
     const float* __restrict__ lg = p.logits + row * p.ld;
     const int begin = chunk * p.chunk_elems;
     const int end = min(p.V, begin + p.chunk_elems);
@@ -423,7 +424,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
 } // namespace
 
 hipError_t launch_accept_sample(const SampleParams& p, hipStream_t s) {
-    hipLaunchKernelGGL(softmax_stats_partial_kernel, dim3(p.chunks, p.B * p.T), dim3(kArgmaxBlock), 0, s, p);
+    hipLaunchKernelGGL(softmax_stats_partial_kernel, dim3((unsigned)((int64_t)p.chunks * p.B * p.T)), dim3(kArgmaxBlock), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(accept_sample_walk_kernel, dim3(p.B), dim3(kWalkThreads), 0, s, p);

@@ -16,6 +16,9 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+} // namespace
+
+namespace vs {
 // Is the current device one this library's kernels were written for? Asked once per device
 // and remembered; called after the argument checks and before the first enqueue.
 int32_t check_device() {
@@ -39,6 +42,9 @@ int32_t check_device() {
     if (dev < kMaxDevices) known[dev].store(ok ? 1 : -1, std::memory_order_relaxed);
     return ok ? VS_OK : VS_ERR_NO_DEVICE;
 }
+} // namespace vs
+
+namespace {
 
 struct Plan {
     int32_t impl, rpw, waves, row_groups, rows, rows_pad, num_splits, keys_per_split, total_wgs, schedule;
@@ -222,7 +228,7 @@ size_t workspace_bytes(const vs_attn_desc* d, const Plan& pl) {
     return align_up(prow * d->d * sizeof(uint16_t)) + align_up(prow * 2 * sizeof(float));
 }
 
-constexpr int kArgmaxChunk = 4096; // floats per workgroup of the scan: 256 threads x 4 x 16 bytes
+constexpr int kArgmaxChunk = kAcceptChunk;
 
 int32_t accept_chunks(int32_t V) { return (V + kArgmaxChunk - 1) / kArgmaxChunk; }
 
@@ -403,7 +409,7 @@ int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V, const 
                        size_t workspace_bytes_given, void* stream) {
     if (!logits || !draft_tokens || !parent || !accepted_len || !path || !bonus_token) return VS_ERR_NULL;
     if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1 || ld_logits < V) return VS_ERR_SHAPE;
-    if ((int64_t)B * T > kMaxGridY) return VS_ERR_SHAPE; // one grid row per logits row
+    if ((int64_t)B * T * accept_chunks(V) > kMaxGridX) return VS_ERR_SHAPE; // one workgroup per (row, chunk)
     const size_t need = vs_accept_workspace_bytes(B, T, V);
     if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;
     if (const int32_t dc = check_device()) return dc;
@@ -443,7 +449,7 @@ int32_t vs_tree_accept_sample(const float* logits, int64_t ld_logits, int32_t V,
     if (!logits || !draft_tokens || !parent || !u_accept || !u_bonus || !accepted_len || !path || !bonus_token)
         return VS_ERR_NULL;
     if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1 || ld_logits < V) return VS_ERR_SHAPE;
-    if (accept_chunks(V) > kMaxSampleChunks || (int64_t)B * T > kMaxGridY) return VS_ERR_SHAPE;
+    if (accept_chunks(V) > kMaxSampleChunks || (int64_t)B * T * accept_chunks(V) > kMaxGridX) return VS_ERR_SHAPE;
     if (!(temperature > 0.f) || !(temperature < INFINITY)) return VS_ERR_SHAPE;
     const size_t need = vs_accept_sample_workspace_bytes(B, T, V);
     if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;
@@ -485,7 +491,7 @@ int32_t vs_draft_expand(const float* logits, int64_t ld_logits, int32_t V, const
                         void* stream) {
     if (!logits || !cand_token || !cand_score || !cand_parent || !next_frontier_cand || !next_cum) return VS_ERR_NULL;
     if (B < 1 || F < 1 || F > VS_MAX_TREE || K < 1 || K > kMaxDraftK || F * K > kMaxDraftCand) return VS_ERR_SHAPE;
-    if (V < K || ld_logits < V || (int64_t)B * F > kMaxGridY) return VS_ERR_SHAPE;
+    if (V < K || ld_logits < V || (int64_t)B * F * accept_chunks(V) > kMaxGridX) return VS_ERR_SHAPE;
     if (cand_base < 0 || cand_capacity < 1 || (int64_t)cand_base + (int64_t)F * K > cand_capacity) return VS_ERR_SHAPE;
     const size_t need = vs_draft_expand_workspace_bytes(B, F, V, K);
     if (!workspace || workspace_bytes_given < need || ((uintptr_t)workspace & (kAlign - 1))) return VS_ERR_WORKSPACE;

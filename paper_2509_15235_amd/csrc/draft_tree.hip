@@ -135,8 +135,9 @@ __global__ __launch_bounds__(kArgmaxBlock) void draft_topk_partial_kernel(const 
     __shared__ int32_t s_ci[(kArgmaxBlock / kWave) * kCandCap];
     __shared__ float s_wv[(kArgmaxBlock / kWave) * kMaxDraftK];
     __shared__ int32_t s_wi[(kArgmaxBlock / kWave) * kMaxDraftK];
-    const int chunk = blockIdx.x;
-    const int64_t row = blockIdx.y;
+    // one-dimensional grid: workgroup id = row * chunks + chunk (the host keeps the product below 2^31)
+    const int64_t row = blockIdx.x / (uint32_t)p.chunks;
+    const int chunk = (int)(blockIdx.x - (uint32_t)row * (uint32_t)p.chunks);
     const float* __restrict__ lg = p.logits + row * p.ld;
     const int begin = chunk * p.chunk_elems;
     const int end = min(p.V, begin + p.chunk_elems);
@@ -452,7 +453,7 @@ __global__ __launch_bounds__(kSelThreads) void draft_tree_build_kernel(const Dra
 } // namespace
 
 hipError_t launch_draft_expand(const DraftExpandParams& p, hipStream_t s) {
-    hipLaunchKernelGGL(draft_topk_partial_kernel, dim3(p.chunks, p.B * p.F), dim3(kArgmaxBlock), 0, s, p);
+    hipLaunchKernelGGL(draft_topk_partial_kernel, dim3((unsigned)((int64_t)p.chunks * p.B * p.F)), dim3(kArgmaxBlock), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(draft_expand_select_kernel, dim3(p.B), dim3(kExpandThreads), 0, s, p);

@@ -14,7 +14,8 @@ namespace vs {
 constexpr int kNumCUs = 256;            // compute units
 constexpr int kNumXCDs = 8;             // accelerator dies; consecutive workgroup ids go round-robin over them
 constexpr int kLdsBytesPerCU = 160 * 1024;
-constexpr int kMaxGridY = 65535;        // largest grid extent in y and z
+constexpr int kMaxGridY = 65535;        // largest grid extent in y and z that every HIP device takes
+constexpr int64_t kMaxGridX = 0x7fffffff; // ... and in x
 constexpr int kManyUnits = 48;          // (sequence, KV head) units from which the straight loop fills the CUs unaided
 
 constexpr int kWave = 64;
@@ -23,6 +24,7 @@ constexpr int kIterKeys = 64;   // keys staged in LDS per loop iteration (two sc
 constexpr int kRowBlock = 32;   // query rows per MFMA row block
 constexpr int kMaxWaves = 8;    // waves per workgroup in the MFMA attention kernel
 constexpr int kArgmaxBlock = 256;
+constexpr int kAcceptChunk = 4096; // floats of a logits row per workgroup of the scans: 256 threads x 4 x 16 bytes
 constexpr int kResidentMaxKeys = 256; // keys of one split that the resident attention kernel keeps in LDS
 
 // Everything the attention kernels need, passed by value.
@@ -160,6 +162,8 @@ inline int32_t validate_tree_host(const int32_t* parent, int32_t T) {
         if (parent[i] < 0 || parent[i] >= i) return VS_STATUS_BAD_PARENT;
     return VS_STATUS_OK;
 }
+
+int32_t check_device(); // VS_OK when the current device is a gfx950, else VS_ERR_NO_DEVICE (api.hip)
 
 hipError_t launch_tree_mask(const int32_t* parent, int32_t B, int32_t T, uint64_t* mask,
                             int32_t* depth, int32_t* status, hipStream_t s);

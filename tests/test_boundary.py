@@ -176,13 +176,14 @@ def test_calls_reject_bad_arguments_before_any_launch():
 
 
 def test_sizes_beyond_a_grid_dimension_are_shape_errors():
-    """One grid row per logits row (or per sequence and KV head): more rows than a grid dimension
-    holds is reported as a shape error on the host, not left to the launch to refuse."""
+    """The logits scans launch one workgroup per (row, 4096-logit chunk) and the split combine one
+    grid row per (sequence, KV head): more than a grid dimension holds is reported as a shape error
+    on the host, not left to the launch to refuse."""
     g = 4096
-    big_b = 65535 // 60 + 1
-    assert vs.vs_tree_accept(g, 10, 10, g, g, big_b, 60, g, g, g, None, None, g, 1 << 30) == -2
-    assert vs.vs_tree_accept_sample(g, 10, 10, 1.0, g, g, g, g, big_b, 60, g, g, g, None, g, 1 << 30) == -2
-    assert vs.vs_draft_expand(g, 100, 100, None, None, 65535 // 8 + 1, 8, 8, 0, 64, g, g, g, g, g, g, 1 << 30) == -2
+    B = 1 << 20                                            # x 64 rows x 38 chunks > 2^31
+    assert vs.vs_tree_accept(g, 152064, 152064, g, g, B, 64, g, g, g, None, None, g, 1 << 40) == -2
+    assert vs.vs_tree_accept_sample(g, 152064, 152064, 1.0, g, g, g, g, B, 64, g, g, g, None, g, 1 << 40) == -2
+    assert vs.vs_draft_expand(g, 152064, 152064, None, None, B, 64, 8, 0, 512, g, g, g, g, g, g, 1 << 40) == -2
     assert vs.vs_attention_plan(_desc(B=65535 // 4 + 1))[0] == -2
 
 
