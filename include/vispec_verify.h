@@ -245,6 +245,27 @@ int32_t vs_tree_accept(const float* logits, int64_t ld_logits, int32_t V,
                        int32_t* row_argmax, int32_t* status, void* workspace,
                        size_t workspace_bytes, void* stream);
 
+/*
+ * vs_tree_accept for callers that cannot allocate or hand over device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, results and error
+ * codes as vs_tree_accept, minus the workspace: the per-chunk scan results live in a static device
+ * array inside the library (VS_ACCEPT_NOALLOC_MAX_BYTES per GPU, held until the process ends). The
+ * call allocates nothing and frees nothing.
+ *   - Sizes whose workspace would exceed the array (vs_accept_workspace_bytes(B,T,V) >
+ *     VS_ACCEPT_NOALLOC_MAX_BYTES, about 131000 (row, 4096-logit chunk) pairs; C5's 16 x 60 rows of
+ *     152064 logits need 292 KB) return VS_ERR_WORKSPACE: use vs_tree_accept for those.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different
+ *     streams, different threads) race and must be ordered by the caller. Calls on different
+ *     GPUs are independent. Nothing in the array has to be cleared between calls.
+ *   - The first call on a device looks up the array's address (no allocation); make it outside
+ *     graph capture.
+ */
+#define VS_ACCEPT_NOALLOC_MAX_BYTES (1u << 20)
+int32_t vs_tree_accept_noalloc(const float* logits, int64_t ld_logits, int32_t V,
+                               const int32_t* draft_tokens, const int32_t* parent, int32_t B, int32_t T,
+                               int32_t* accepted_len, int32_t* path, int32_t* bonus_token,
+                               int32_t* row_argmax, int32_t* status, void* stream);
+
 size_t vs_accept_sample_workspace_bytes(int32_t B, int32_t T, int32_t V); /* 0 for unsupported sizes */
 
 /*

@@ -16,7 +16,7 @@ VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED, VS_SCHED_RESIDENT = 0, 1, 2, 3
 EXPORTED_SYMBOLS = [
     "vs_version", "vs_strerror", "vs_status_string", "vs_tree_validate_host", "vs_tree_mask_build",
     "vs_attention_plan", "vs_attention_workspace_bytes", "vs_tree_verify_attention",
-    "vs_accept_workspace_bytes", "vs_tree_accept", "vs_accept_sample_workspace_bytes", "vs_tree_accept_sample",
+    "vs_accept_workspace_bytes", "vs_tree_accept", "vs_tree_accept_noalloc", "vs_accept_sample_workspace_bytes", "vs_tree_accept_sample",
     "vs_draft_expand_workspace_bytes", "vs_draft_expand", "vs_draft_tree_build", "vs_tree_kv_commit",
     "vs_compress_attention_workspace_bytes", "vs_compress_attention",
 ]
@@ -101,6 +101,8 @@ def lib():
         L.vs_accept_workspace_bytes.restype = sz
         L.vs_tree_accept.argtypes = [vp, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vs_tree_accept.restype = i32
+        L.vs_tree_accept_noalloc.argtypes = [vp, i64, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.vs_tree_accept_noalloc.restype = i32
         L.vs_accept_sample_workspace_bytes.argtypes = [i32, i32, i32]
         L.vs_accept_sample_workspace_bytes.restype = sz
         L.vs_tree_accept_sample.argtypes = [vp, i64, i32, ctypes.c_float, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp,
@@ -188,6 +190,13 @@ def vs_tree_accept(logits, ld_logits, V, draft_tokens, parent, B, T, accepted_le
     return lib().vs_tree_accept(_ptr(logits), ld_logits, V, _ptr(draft_tokens), _ptr(parent), B, T,
                                 _ptr(accepted_len), _ptr(path), _ptr(bonus_token), _ptr(row_argmax),
                                 _ptr(status), _ptr(workspace), workspace_bytes, _ptr(stream))
+
+
+def vs_tree_accept_noalloc(logits, ld_logits, V, draft_tokens, parent, B, T, accepted_len, path, bonus_token,
+                           row_argmax=None, status=None, stream=None) -> int:
+    return lib().vs_tree_accept_noalloc(_ptr(logits), ld_logits, V, _ptr(draft_tokens), _ptr(parent), B, T,
+                                        _ptr(accepted_len), _ptr(path), _ptr(bonus_token), _ptr(row_argmax),
+                                        _ptr(status), _ptr(stream))
 
 
 def vs_accept_sample_workspace_bytes(B: int, T: int, V: int) -> int:

@@ -5,7 +5,16 @@
 // Two kernels: (1) a bandwidth-bound scan that reduces each logits row to per-chunk
 // (max, first index) pairs, (2) one workgroup per sequence that finishes the row argmax
 // and walks the tree.
+#include <atomic>
+
 #include "vs_device.h"
+
+// Scratch of vs_tree_accept_noalloc: the per-(row, chunk) results that vs_tree_accept keeps in the
+// caller's workspace. One copy per GPU, held until the process ends. In host code the array's
+// name is only a handle for hipGetSymbolAddress: the device address is asked for once per device
+// and everything that touches the memory uses that address.
+constexpr size_t kNoallocScratchBytes = VS_ACCEPT_NOALLOC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
 
 namespace vs {
 
@@ -197,6 +206,27 @@ __global__ __launch_bounds__(256) void accept_walk_kernel(const AcceptParams p) 
     }
 }
 
+constexpr int kMaxDevices = 64;
+std::atomic<void*> scratch_of[kMaxDevices]; // device address of `scratch` on each device, null = not asked yet
+
+// Device address of the current device's copy of `scratch`; asks the runtime on the first call
+// per device. Returns null (and leaves no sticky error) when that fails.
+void* scratch_address() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    void* ptr = scratch_of[dev].load(std::memory_order_acquire);
+    if (ptr) return ptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    scratch_of[dev].store(ptr, std::memory_order_release);
+    return ptr;
+}
+
 } // namespace
 
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s) {
@@ -208,3 +238,40 @@ hipError_t launch_accept(const AcceptParams& p, hipStream_t s) {
 }
 
 } // namespace vs
+
+extern "C" int32_t vs_tree_accept_noalloc(const float* logits, int64_t ld_logits, int32_t V, const int32_t* draft_tokens,
+                                          const int32_t* parent, int32_t B, int32_t T, int32_t* accepted_len,
+                                          int32_t* path, int32_t* bonus_token, int32_t* row_argmax, int32_t* status,
+                                          void* stream) {
+    using namespace vs;
+    if (!logits || !draft_tokens || !parent || !accepted_len || !path || !bonus_token) return VS_ERR_NULL;
+    if (B < 1 || T < 1 || T > VS_MAX_TREE || V < 1 || ld_logits < V) return VS_ERR_SHAPE;
+    const size_t need = vs_accept_workspace_bytes(B, T, V);
+    if (need == 0 || need > kNoallocScratchBytes) return VS_ERR_WORKSPACE; // beyond the static scratch: use vs_tree_accept
+    if (const int32_t dc = check_device()) return dc;
+    unsigned char* ws = (unsigned char*)scratch_address();
+    if (!ws) return VS_ERR_HIP;
+    // same layout as vs_tree_accept's workspace: values, then (256-byte aligned) indices. Nothing
+    // has to start at zero: the scan writes every pair the walk reads.
+    const int32_t chunks = (V + kAcceptChunk - 1) / kAcceptChunk;
+    const size_t n = (size_t)B * T * chunks;
+    AcceptParams p{};
+    p.logits = logits;
+    p.ld = ld_logits;
+    p.V = V;
+    p.draft = draft_tokens;
+    p.parent = parent;
+    p.B = B;
+    p.T = T;
+    p.accepted_len = accepted_len;
+    p.path = path;
+    p.bonus = bonus_token;
+    p.row_argmax = row_argmax;
+    p.status = status;
+    p.chunks = chunks;
+    p.chunk_elems = kAcceptChunk;
+    p.vec_ok = (((uintptr_t)logits & 15u) == 0 && ld_logits % 4 == 0) ? 1 : 0;
+    p.part_val = (float*)ws;
+    p.part_idx = (int32_t*)(ws + (n * sizeof(float) + 255) / 256 * 256);
+    return launch_accept(p, (hipStream_t)stream) == hipSuccess ? VS_OK : VS_ERR_HIP;
+}
