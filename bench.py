@@ -38,10 +38,118 @@ def parse():
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate over (0 = enough to exceed 512 MB)")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every launch from Python instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the attention legs of the other configurations (C2 / C4 folded, C5 ragged batch)")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--folded-splits", type=int, default=0)
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
+
+
+def other_config_leg(vs, gen, torch, dev, stream, gtorch, name, seed, check, oracle_depths=None):
+    """Attention of one of the other configurations on device-generated data; returns a roofline block.
+    C2 / C4: the L layers folded into one launch (contiguous caches); C5: one layer of the ragged batch
+    over a paged cache with a shuffled block table."""
+    import numpy as np
+    cfg = gen.CONFIGS[name]
+    T, Hq, Hkv, d, eb = cfg.T, cfg.Hq, cfg.Hkv, cfg.d, 2
+    scale = 1.0 / np.sqrt(d)
+    sp = stream.cuda_stream
+    if cfg.paged:
+        S_b, _ = gen.draw_prefix(cfg, seed)
+        B = cfg.B
+        parent_h = gen.draw_trees(cfg, seed)
+        bs = cfg.block_size
+        nblk = (S_b.astype(np.int64) + T + bs - 1) // bs
+        n_blocks = int(nblk.sum()) + 3
+        perm = gen.rng(seed, gen.STREAM_BLOCKS).permutation(n_blocks).astype(np.int32)
+        max_blocks = int(nblk.max()) + 1
+        table_h = np.zeros((B, max_blocks), dtype=np.int32)
+        at = 0
+        for b in range(B):
+            table_h[b, :nblk[b]] = perm[at:at + nblk[b]]
+            at += int(nblk[b])
+        table = torch.from_numpy(table_h).to(dev)
+        kv_shape = (n_blocks, Hkv, bs, d)
+        launch = f"one layer of the ragged batch: B={B}, prefixes {int(S_b.min())}..{int(S_b.max())}, paged cache"
+        layers_per_call = 1
+    else:
+        B = cfg.layers
+        S_b = np.full(B, cfg.prefix[0], dtype=np.int32)
+        parent_h = np.repeat(gen.draw_trees(cfg, seed), B, axis=0)
+        cap = int(S_b[0]) + T + 4
+        kv_shape = (B, Hkv, cap, d)
+        table = None
+        launch = f"B={B} proxy: {B} layers folded into one launch as independent batch entries"
+        layers_per_call = B
+    kv_bytes = 2 * int(np.prod(kv_shape)) * eb
+    nsets = max(2, int(np.ceil(600e6 / kv_bytes)))
+    sets = []
+    for _ in range(nsets):
+        sets.append(dict(
+            q=torch.randn((B, T, Hq, d), generator=gtorch, device=dev, dtype=torch.float32).to(torch.bfloat16),
+            k=torch.randn(kv_shape, generator=gtorch, device=dev, dtype=torch.float32).to(torch.bfloat16),
+            v=torch.randn(kv_shape, generator=gtorch, device=dev, dtype=torch.float32).to(torch.bfloat16),
+            out=torch.empty((B, T, Hq, d), device=dev, dtype=torch.bfloat16)))
+    desc = vs.AttnDesc(B=B, T=T, Hq=Hq, Hkv=Hkv, d=d, dtype=vs.VS_BF16, softmax_scale=float(scale),
+                       max_prefix_len=int(S_b.max()), impl=vs.VS_IMPL_AUTO)
+    if cfg.paged:
+        desc.paged, desc.block_size, desc.max_blocks, desc.num_blocks = 1, bs, max_blocks, n_blocks
+        desc.stride_block, desc.stride_head, desc.stride_tok = Hkv * bs * d, bs * d, d
+        desc.block_table = table.data_ptr()
+    else:
+        desc.paged, desc.capacity = 0, cap
+        desc.stride_seq, desc.stride_head, desc.stride_tok = Hkv * cap * d, cap * d, d
+    rc, plan = vs.vs_attention_plan(desc)
+    assert rc == 0
+    ws_bytes = max(vs.vs_attention_workspace_bytes(desc), 256)
+    ws = torch.empty(ws_bytes, device=dev, dtype=torch.uint8)
+    parent = torch.from_numpy(parent_h.astype(np.int32)).to(dev)
+    prefix = torch.from_numpy(S_b.astype(np.int32)).to(dev)
+    mask = torch.zeros((B, T), device=dev, dtype=torch.int64)
+    depth = torch.zeros((B, T), device=dev, dtype=torch.int32)
+    status = torch.zeros((B,), device=dev, dtype=torch.int32)
+    check(vs.vs_tree_mask_build(parent, B, T, mask, depth, status, sp))
+    stream.synchronize()
+    depth_h = depth.cpu().numpy()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        for st in sets:
+            check(vs.vs_tree_verify_attention(desc, st["q"], st["k"], st["v"], prefix, parent, mask, st["out"], status,
+                                              ws, ws_bytes, torch.cuda.current_stream().cuda_stream))
+    with torch.cuda.stream(stream):
+        t_end = time.perf_counter() + 0.15                                               # let the clocks settle
+        while time.perf_counter() < t_end:
+            g.replay()
+            stream.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        reps = 40
+        e0.record(stream)
+        for _ in range(reps):
+            g.replay()
+        e1.record(stream)
+        stream.synchronize()
+    ms = e0.elapsed_time(e1) / reps / nsets
+    assert int(status.abs().max().item()) == 0
+    vis_pairs = int(sum(int(S_b[b]) + int(dd) + 1 for b in range(B) for dd in depth_h[b]))
+    flops = 4.0 * d * Hq * vis_pairs
+    nbytes = float(sum(2.0 * Hkv * (int(S_b[b]) + T) * d * eb for b in range(B)) + 2.0 * B * T * Hq * d * eb)
+    t_mfma, t_hbm = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+    tf, gbs = flops / (ms * 1e-3) / 1e12, nbytes / (ms * 1e-3) / 1e9
+    blk = {"bound": "mfma" if t_mfma >= t_hbm else "hbm"}
+    if blk["bound"] == "mfma":
+        blk.update({"achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)})
+    else:
+        blk.update({"achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)})
+    sched = {vs.VS_SCHED_PIPELINED: "attn_mfma_pipe_kernel", vs.VS_SCHED_RESIDENT: "attn_mfma_resident_kernel"}.get(plan.schedule, "attn_mfma_kernel")
+    blk.update({"traffic": None, "workload": cfg.name, "launch": launch, "us_per_launch": round(ms * 1e3, 2),
+                "tflops": round(tf, 2), "hbm_gbs": round(gbs, 1), "workgroups": plan.workgroups, "num_splits": plan.num_splits,
+                "kernel": sched + (" + attn_combine_kernel" if plan.combine else ""),
+                "layers_per_launch": layers_per_call, "buffer_sets": nsets, "data": "device-generated N(0,1)"})
+    del sets
+    torch.cuda.empty_cache()
+    return blk
 
 
 def main():
@@ -328,13 +436,57 @@ def main():
     ms_commit = per_call(enqueue_commit, max(args.steps // 2, 25), max(args.warmup, 5))
     ms_compress = per_call(enqueue_compress, max(args.steps // 2, 25), max(args.warmup, 5))
 
-    # a plain device copy of known size: the reference that scales rocprofv3's FETCH_SIZE /
-    # WRITE_SIZE counters when HBM traffic of the kernels above is derived from a --pmc run
-    cal_src = torch.empty(256 << 20, device=dev, dtype=torch.uint8)
+    # ---------------------------------------------------------------- what the machine delivers (measured peaks)
+    # Trivial kernels of the library (include/vispec_peaks.h), timed like the legs above. The copy of
+    # known size is also the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters when
+    # the HBM traffic of the kernels above is derived from a --pmc run.
+    peak_bytes = 1 << 30
+    cal_src = torch.randint(0, 255, (peak_bytes,), device=dev, dtype=torch.uint8)
     cal_dst = torch.empty_like(cal_src)
-    with torch.cuda.stream(stream):
-        cal_dst.copy_(cal_src)
-    stream.synchronize()
+    sink = torch.zeros(65536 * 512, device=dev, dtype=torch.float32)
+    ops_const = torch.full((8 * 128 * 8,), 1.0, device=dev, dtype=torch.bfloat16)
+    ops_rand = torch.randn((8 * 128 * 8,), generator=gtorch, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    mfma_iters, mfma_wgs = 2000, 256
+
+    def time_calls(fn, reps, warm):
+        with torch.cuda.stream(stream):
+            for _ in range(warm):
+                fn()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            stream.synchronize()
+        return e0.elapsed_time(e1) / reps                                              # ms per call
+
+    ms_read = time_calls(lambda: check(vs.vs_peak_hbm_read(cal_src, peak_bytes, sink, 8192, sp)), 20, 5)
+    ms_copy = time_calls(lambda: check(vs.vs_peak_hbm_copy(cal_dst, cal_src, peak_bytes // 2, 8192, sp)), 20, 5)
+    # the matrix-core loops run ~100 ms each so that the clocks settle (see the folded leg)
+    ms_mc = time_calls(lambda: check(vs.vs_peak_mfma_bf16(ops_const, mfma_iters, sink, mfma_wgs, sp)), 60, 60)
+    ms_mr = time_calls(lambda: check(vs.vs_peak_mfma_bf16(ops_rand, mfma_iters, sink, mfma_wgs, sp)), 60, 60)
+    mfma_flops = vs.vs_peak_mfma_flops(mfma_iters, mfma_wgs)
+    measured_peaks = {
+        "hbm_read_gbs": round(peak_bytes / (ms_read * 1e-3) / 1e9, 1),
+        "hbm_copy_gbs": round(2 * (peak_bytes // 2) / (ms_copy * 1e-3) / 1e9, 1),
+        "mfma_bf16_const_tflops": round(mfma_flops / (ms_mc * 1e-3) / 1e12, 1),
+        "mfma_bf16_random_tflops": round(mfma_flops / (ms_mr * 1e-3) / 1e12, 1),
+        "note": "vs_peak_* kernels: 1 GiB streaming read, 512 MiB copy (read + write counted), 2048 waves of "
+                "v_mfma_f32_32x32x16_bf16 on all-ones / on N(0,1) operands; nominal peaks 8000 GB/s and 2500 TFLOP/s",
+    }
+    del cal_dst
+
+    # ---------------------------------------------------------------- the other configurations' attention
+    # Shapes of the benchmark's other configurations on device-generated N(0,1) data (their parity is
+    # the GPU tests' business): C2 and C4 with their layers folded into one launch like `roofline`,
+    # C5 as it is (16 ragged sequences over a paged cache need no folding: one layer is one launch).
+    others = {}
+    if not args.no_other_configs:
+        for name in ("C2", "C4", "C5"):
+            if name == args.config:
+                continue
+            others[name] = other_config_leg(vs, gen, torch, dev, stream, gtorch, name, args.seed, check, oracle_depths=None)
 
     # ---------------------------------------------------------------- algorithmic work
     _, _, depth_h = oracle.tree_mask(parent_h[0])
@@ -360,23 +512,31 @@ def main():
     # same command; the summary and its scaling are under profiles/)
     try:
         with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")) as f:
-            roofline["traffic"] = json.load(f).get(args.config, {}).get("folded_attention_call_bytes")
+            traffic = json.load(f)
+        roofline["traffic"] = traffic.get(args.config, {}).get("folded_attention_call_bytes")
+        roofline["traffic_source"] = "profiles/hbm_traffic.json: " + traffic.get("_source", "rocprofv3 --pmc runs of this command")
     except OSError:
-        pass
+        roofline["traffic_source"] = "not measured"
     def kernel_name(pl):
         k = {vs.VS_SCHED_PIPELINED: "attn_mfma_pipe_kernel", vs.VS_SCHED_RESIDENT: "attn_mfma_resident_kernel"}.get(
             pl.schedule, "attn_mfma_kernel")
         return k + (" + attn_combine_kernel" if pl.combine else "")
 
-    roofline.update({"kernel": kernel_name(planL), "launch": f"{L} layers folded as batch entries",
+    roofline.update({"kernel": kernel_name(planL),
+                     "launch": f"B={L} proxy: the step's {L} layers folded into one launch as independent batch entries "
+                               "(same per-layer shape; layers of a real model are sequentially dependent, so the timed "
+                               "step issues `per_layer_call` instead)",
                      "us_per_launch": round(ms_folded * 1e3, 2), "workgroups": planL.workgroups,
                      "num_splits": planL.num_splits,
                      "tflops": round(flops_layer * L / (ms_folded * 1e-3) / 1e12, 2),
                      "hbm_gbs": round(bytes_layer * L / (ms_folded * 1e-3) / 1e9, 1),
                      "frac_of_hbm_peak": round(bytes_layer * L / (ms_folded * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
     per_layer = roof(ms_single, 1)
-    per_layer.update({"launch": "one layer, B=1", "us_per_launch": round(ms_single * 1e3, 2),
-                      "workgroups": plan1.workgroups, "num_splits": plan1.num_splits, "kernel": kernel_name(plan1)})
+    per_layer.update({"launch": "one layer, B=1: the call the timed step issues once per layer", "us_per_launch": round(ms_single * 1e3, 2),
+                      "workgroups": plan1.workgroups, "num_splits": plan1.num_splits, "kernel": kernel_name(plan1),
+                      "algorithmic_bytes": int(bytes_layer), "workspace_bytes": int(vs.vs_attention_workspace_bytes(desc1))})
+    for blk in (roofline, per_layer):
+        blk["frac_of_measured_mfma_random"] = round(blk["achieved"] / measured_peaks["mfma_bf16_random_tflops"], 4) if bound == "mfma" else None
     argmax_gbs = logit_bytes / (ms_accept * 1e-3) / 1e9
     argmax = {"bound": "hbm", "achieved": round(argmax_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
               "frac": round(argmax_gbs / HBM_PEAK_GBS, 4), "us_per_launch": round(ms_accept * 1e3, 2),
@@ -408,8 +568,16 @@ def main():
             oracle.tree_attention(host_layers[l], threads=threads)
         oracle.tree_accept(acc_h.logits, acc_h.tokens, acc_h.parent)
         tc = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.tree_attention(host_layers[0], threads=1)
+        t1 = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.tree_accept(acc_h.logits, acc_h.tokens, acc_h.parent)
+        ta = time.perf_counter() - t0
         cpu = {"value": round(1.0 / tc, 4), "unit": "steps/s", "cores": threads, "kind": "oracle",
-               "sample": f"one full step of {cfg.name}: {L} layers of fp64 attention + one accept, {tc:.2f} s"}
+               "sample": f"one full step of {cfg.name}: {L} layers of fp64 attention + one accept, {tc:.2f} s",
+               "one_thread_s": round(L * t1 + ta, 2),
+               "one_thread_sample": f"one layer of attention on one thread ({t1:.2f} s) x {L} + one accept ({ta:.3f} s), extrapolated"}
 
     line = {
         "metric": "verify steps/sec (tree-verify attention TFLOP/s and HBM GB/s as % of roofline in `roofline`)",
@@ -420,6 +588,7 @@ def main():
                                f"layers={L} vocab={V}; step = mask_build + {L} x attention + accept",
                    "hip_graph": not args.no_graph, "buffer_sets": nsets},
         "roofline": roofline, "per_layer_call": per_layer, "argmax": argmax, "accept_sample": sample, "draft_tree": draft, "compress_attention": compress, "kv_commit": commit, "cpu_baseline": cpu,
+        "measured_peaks": measured_peaks, "other_configs": others,
         "parity": {"attention_max_abs_err_layer0": err0, "accept_bit_exact": accept_ok, "commit_bit_exact": commit_ok,
                    "sample_outcome_valid": sample_ok, "draft_tree_bit_exact": draft_ok,
                    "compress_attention_max_abs_err": err_c},

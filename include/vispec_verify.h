@@ -83,7 +83,7 @@ typedef enum vs_attn_impl { VS_IMPL_AUTO = 0, VS_IMPL_GENERIC = 1, VS_IMPL_MFMA 
 /* How the MFMA kernels are scheduled. LOOP streams 64-key tiles through LDS and runs a tile's
  * three stages (scores, softmax, output update) back to back; PIPELINED overlaps the matrix-core
  * work of the neighbouring tiles with the current tile's softmax (launches with many units);
- * RESIDENT copies a split's whole key range (at most 256 keys) into LDS first and splits the
+ * RESIDENT keeps a split's whole key range (at most 192 keys) in LDS and splits the
  * keys once more among the waves of a workgroup (latency-bound launches with few units).
  * Same results up to fp32 rounding. AUTO chooses from the shape. */
 typedef enum vs_attn_schedule {
@@ -155,7 +155,7 @@ typedef struct vs_attn_desc {
     int32_t waves_per_group; /* MFMA path: waves per workgroup, 1, 2, 4 or 8; 0 = choose */
     int32_t schedule;       /* MFMA path: vs_attn_schedule; PIPELINED needs rows_per_wave 0 or 1
                                and waves_per_group 0, 4 or 8; RESIDENT needs rows_per_wave 0 or 1 and
-                               waves_per_group 0 or 8, and never puts more than 256 keys into a split
+                               waves_per_group 0 or 8, and never puts more than 192 keys into a split
                                (num_splits is raised where it asks for more) */
 } vs_attn_desc;
 

@@ -14,4 +14,5 @@ from .binding import (  # noqa: F401
     vs_accept_workspace_bytes, vs_tree_accept, vs_tree_accept_noalloc, vs_accept_sample_workspace_bytes, vs_tree_accept_sample,
     vs_compress_attention_workspace_bytes, vs_compress_attention,
     vs_draft_expand_workspace_bytes, vs_draft_expand, vs_draft_tree_build, vs_tree_kv_commit, EXPORTED_SYMBOLS,
+    PEAK_SYMBOLS, vs_peak_hbm_read, vs_peak_hbm_copy, vs_peak_mfma_bf16, vs_peak_mfma_flops,
 )

@@ -20,6 +20,8 @@ EXPORTED_SYMBOLS = [
     "vs_draft_expand_workspace_bytes", "vs_draft_expand", "vs_draft_tree_build", "vs_tree_kv_commit",
     "vs_compress_attention_workspace_bytes", "vs_compress_attention",
 ]
+# measurement helpers declared in include/vispec_peaks.h
+PEAK_SYMBOLS = ["vs_peak_hbm_read", "vs_peak_hbm_copy", "vs_peak_mfma_bf16", "vs_peak_mfma_flops"]
 
 
 class VSError(RuntimeError):
@@ -116,6 +118,14 @@ def lib():
         L.vs_draft_tree_build.restype = i32
         L.vs_tree_kv_commit.argtypes = [ctypes.POINTER(KVDesc), vp, vp, vp, vp, vp, vp, vp, vp]
         L.vs_tree_kv_commit.restype = i32
+        L.vs_peak_hbm_read.argtypes = [vp, sz, vp, i32, vp]
+        L.vs_peak_hbm_read.restype = i32
+        L.vs_peak_hbm_copy.argtypes = [vp, vp, sz, i32, vp]
+        L.vs_peak_hbm_copy.restype = i32
+        L.vs_peak_mfma_bf16.argtypes = [vp, i32, vp, i32, vp]
+        L.vs_peak_mfma_bf16.restype = i32
+        L.vs_peak_mfma_flops.argtypes = [i32, i32]
+        L.vs_peak_mfma_flops.restype = ctypes.c_double
         _lib = L
     return _lib
 
@@ -236,3 +246,19 @@ def vs_tree_kv_commit(desc: KVDesc, k_cache, v_cache, prefix_len, path, accepted
                       status=None, stream=None) -> int:
     return lib().vs_tree_kv_commit(ctypes.byref(desc), _ptr(k_cache), _ptr(v_cache), _ptr(prefix_len), _ptr(path),
                                    _ptr(accepted_len), _ptr(new_prefix_len), _ptr(status), _ptr(stream))
+
+
+def vs_peak_hbm_read(src, nbytes: int, sink, workgroups: int, stream=None) -> int:
+    return lib().vs_peak_hbm_read(_ptr(src), nbytes, _ptr(sink), workgroups, _ptr(stream))
+
+
+def vs_peak_hbm_copy(dst, src, nbytes: int, workgroups: int, stream=None) -> int:
+    return lib().vs_peak_hbm_copy(_ptr(dst), _ptr(src), nbytes, workgroups, _ptr(stream))
+
+
+def vs_peak_mfma_bf16(operands, iters: int, sink, workgroups: int, stream=None) -> int:
+    return lib().vs_peak_mfma_bf16(_ptr(operands), iters, _ptr(sink), workgroups, _ptr(stream))
+
+
+def vs_peak_mfma_flops(iters: int, workgroups: int) -> float:
+    return lib().vs_peak_mfma_flops(iters, workgroups)

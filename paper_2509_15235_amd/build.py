@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvispec_verify.so")
 SOURCES = ["api.hip", "tree_mask.hip", "attention_generic.hip", "attention_mfma.hip", "attention_mfma_pipe.hip", "attention_mfma_resident.hip", "accept.hip", "accept_sample.hip", "draft_tree.hip",
-           "kv_commit.hip"]
+           "kv_commit.hip", "peaks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -135,16 +135,19 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     const bool many = units0 >= 12; // enough (sequence, KV head) units for the pipelined kernel, see below
     // few units, several row blocks, a short sequence (at most 2048 keys) and no caller's
     // choice that it cannot honour: the LDS-resident kernel, whose second split of the keys
-    // among the waves shortens each workgroup's loop. Measured on C3-sized layers replayed from
-    // a HIP graph over 400 MB of K/V (every layer cold in the caches): 19.0 us per layer with
-    // 10 splits, the streaming loop 19.2 us; slower than the loop for two row blocks and for
-    // 5000+ keys, where its 256-key limit forces too many partial results.
-    // ... and only while all its workgroups (128 KB of LDS each: one per CU) run at once: with two
-    // sequences (320 workgroups) it already takes 30.7 us against the loop's 24.6, with eleven 85 against 51.
-    const int res_splits = splits > 0 ? splits : (tiles + 2) / 3;
+    // among the waves shortens each workgroup's loop - as long as all its workgroups (up to 96 KB
+    // of LDS each: one per CU) run at once. Splits of two 64-key tiles when that fits, else
+    // three. Measured on C3-sized layers replayed from a HIP graph over 400 MB of K/V (every
+    // layer cold in the caches), per layer: 14 splits of 128 keys 15.8 us, 10 splits of 192 keys
+    // 16.7 us; the streaming loop with the same splits 15.7 / 16.9 us. With two sequences (more
+    // workgroups than CUs) it loses to the loop, and for 5000+ keys its 192-key limit forces too
+    // many partial results.
+    const int res_rg = (nrb + 3) / 4;
+    const int res_tps = (int64_t)units0 * res_rg * ((tiles + 1) / 2) <= kNumCUs ? 2 : 3; // 64-key tiles per split
+    const int res_splits = splits > 0 ? splits : (tiles + res_tps - 1) / res_tps;
     const bool resident_ok = !many && nrb >= 3 && tiles <= 32 && (rpw == 0 || rpw == 1) && (waves == 0 || waves == 8) &&
                              (splits <= 0 || (tiles + splits - 1) / splits <= kResidentMaxKeys / kIterKeys) &&
-                             (int64_t)units0 * ((nrb + 3) / 4) * res_splits <= kNumCUs;
+                             (int64_t)units0 * res_rg * res_splits <= kNumCUs;
     // The pipelined kernel takes over from twelve units on (three C3 sequences, or one MHA
     // layer): A/B per call, loop against pipelined, 3 sequences 26.3 / 24.9 us, 4: 28.6 / 26.9,
     // 6: 34.0 / 29.7, 8: 39.9 / 31.4, 11: 50.9 / 39.9, one C2 (MHA) layer 25.4 / 23.3; below
@@ -155,13 +158,13 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
                                                : VS_SCHED_LOOP;
     if (pl.schedule == VS_SCHED_RESIDENT) {
         // eight waves = res_rb row blocks x 8 / res_rb key parts; a split holds at most
-        // kResidentMaxKeys keys (four 64-key tiles)
+        // kResidentMaxKeys keys (three 64-key tiles)
         pl.rpw = 1;
         pl.waves = 8;
         pl.res_rb = nrb >= 3 ? 4 : nrb;
         pl.row_groups = (nrb + pl.res_rb - 1) / pl.res_rb;
         const int max_tiles = kResidentMaxKeys / kIterKeys;
-        if (splits <= 0) splits = (tiles + 2) / 3; // three 64-key tiles per split (measured: 19.0 us per C3 layer; four: 19.6)
+        if (splits <= 0) splits = res_splits;
         int tps = (tiles + splits - 1) / splits;
         if (tps > max_tiles) tps = max_tiles;
         if (tps < 1) tps = 1;
@@ -354,7 +357,7 @@ int32_t enqueue_attention(const vs_attn_desc* desc, int tree, const void* q, con
     p.num_splits = pl.num_splits;
     p.keys_per_split = pl.keys_per_split;
     p.row_groups = pl.row_groups;
-    p.rows_per_group = pl.waves * pl.rpw * kRowBlock;
+    p.rows_per_group = (pl.schedule == VS_SCHED_RESIDENT ? pl.res_rb : pl.waves * pl.rpw) * kRowBlock;
     p.total_wgs = pl.total_wgs;
     if (need > 0) {
         const size_t prow = (size_t)desc->B * desc->Hkv * pl.num_splits * pl.rows_pad;

@@ -89,16 +89,20 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     const int half = lane >> 5;
     const int col = lane & 31;
 
-    // Workgroup id -> (sequence, KV head, split, row group). Consecutive hardware ids go
-    // round-robin over the 8 XCDs; the remap keeps workgroups that read the same K/V
-    // (row groups, then neighbouring splits) on one XCD so they share its L2.
+    // Workgroup id -> (sequence, KV head, row group, split). Consecutive hardware ids go
+    // round-robin over the 8 XCDs; the remap gives every XCD a contiguous range of work, so the
+    // workgroups of one (sequence, KV head) share an XCD's L2 for their K/V as far as they fit,
+    // and - splits being the fastest index - all key splits of a row group run on one XCD, whose
+    // L2 then holds the partial results that the combine workgroups of those rows (placed by the
+    // same remap) read. Measured on one C3 layer: 19.0 -> 16.7 us per call against an order with
+    // the row groups fastest, whose partials came from two XCDs.
     const int per_xcd = (p.total_wgs + 7) >> 3;
     const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (v >= p.total_wgs) return;
-    const int rg = v % p.row_groups;
-    int rest = v / p.row_groups;
-    const int split = rest % p.num_splits;
-    rest /= p.num_splits;
+    const int split = v % p.num_splits;
+    int rest = v / p.num_splits;
+    const int rg = rest % p.row_groups;
+    rest /= p.row_groups;
     const int kvh = rest % p.Hkv;
     const int b = rest / p.Hkv;
 
@@ -485,9 +489,21 @@ template <int D>
 __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p) {
     constexpr int DB = D / 32;
     __shared__ __attribute__((aligned(16))) uint16_t so[kRowBlock][32 + 8];
-    const int unit = blockIdx.y;
+    // Workgroup id -> (unit, row group, row block of the group, channel block), in contiguous ranges
+    // per XCD like the main kernels: the partials of a row group's splits were written through the L2
+    // of the XCD that ran them, and with splits as the main kernel's fastest index (resident schedule)
+    // that is the XCD these rows' combine workgroups land on.
+    const int rbg = p.rows_per_group / kRowBlock; // row blocks per row group
+    const int items = p.B * p.Hkv * p.row_groups * rbg * DB;
+    const int per_xcd = (items + 7) >> 3;
+    const int vi = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (vi >= items) return;
+    const int db = vi % DB;
+    int rest = vi / DB;
+    const int rbk = (rest / rbg % p.row_groups) * rbg + rest % rbg;
+    const int unit = rest / (rbg * p.row_groups);
+    if (rbk * kRowBlock >= p.rows) return; // padding of the last row group
     const int b = unit / p.Hkv, kvh = unit % p.Hkv;
-    const int rbk = blockIdx.x / DB, db = blockIdx.x % DB;
     const int lane = threadIdx.x, col = lane & 31, half = lane >> 5;
     const int32_t S = p.prefix_len[b];
     const f32x2* gml = (const f32x2*)p.part_ml + ml_block(p, unit, 0, rbk) + col; // + s * kRowBlock
@@ -583,7 +599,8 @@ hipError_t launch_attention_mfma(const AttnParams& p, int rpw, int waves, hipStr
 
 hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t s) {
     (void)dtype;
-    const dim3 grid((p.rows_pad / kRowBlock) * (p.d / 32), p.B * p.Hkv);
+    const int items = p.B * p.Hkv * p.row_groups * (p.rows_per_group / kRowBlock) * (p.d / 32);
+    const dim3 grid((unsigned)((items + 7) / 8 * 8));
     if (p.d == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), grid, dim3(kWave), 0, s, p);
     else if (p.d == 64) hipLaunchKernelGGL((attn_combine_kernel<64>), grid, dim3(kWave), 0, s, p);
     else return hipErrorInvalidValue;

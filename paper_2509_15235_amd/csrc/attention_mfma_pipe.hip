@@ -55,14 +55,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     const int half = lane >> 5;
     const int col = lane & 31;
 
-    // workgroup id -> (sequence, KV head, split, row group), XCD-aware (see attention_mfma.hip)
+    // workgroup id -> (sequence, KV head, row group, split), XCD-aware (see attention_mfma.hip)
     const int per_xcd = (p.total_wgs + 7) >> 3;
     const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (v >= p.total_wgs) return;
-    const int rg = v % p.row_groups;
-    int rest = v / p.row_groups;
-    const int split = rest % p.num_splits;
-    rest /= p.num_splits;
+    const int split = v % p.num_splits; // splits fastest, see attention_mfma.hip
+    int rest = v / p.num_splits;
+    const int rg = rest % p.row_groups;
+    rest /= p.row_groups;
     const int kvh = rest % p.Hkv;
     const int b = rest / p.Hkv;
 

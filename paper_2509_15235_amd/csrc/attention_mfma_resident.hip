@@ -10,12 +10,17 @@
 // wave per SIMD the streaming kernel spends 2 us per 64-key iteration of which the matrix cores
 // work 0.4 us - the rest is a single wave issuing its tile copy, LDS writes, barrier and
 // softmax one dependent instruction after the other. Here a workgroup of eight waves owns
-// NRB row blocks x KQ = 8 / NRB key parts: all waves first copy the split's keys and values
-// (at most 256 keys, 128 KB) into LDS with every load in flight at once, then each wave runs
-// its key part for its row block with no further copies or barriers (two waves per SIMD cover
-// each other's stalls), and the key parts are merged through LDS (log-sum-exp, like the
-// combine kernel does for the splits). Split partials and final rows leave as in the
-// streaming kernels, so the combine kernel and the workspace layout are shared.
+// NRB row blocks x KQ = 8 / NRB key parts of a split of NT 32-key tiles (at most 192 keys,
+// 96 KB). Every load of the split is issued at once, before anything is waited for, ordered by
+// stage: stage j holds the j-th tile of every key part. As soon as a stage has arrived it goes
+// into LDS (one barrier) and every wave runs that tile for its row block while the later stages
+// are still on their way (wall-clock stamps of the earlier form - all loads, one barrier, then
+// all tiles - showed 3.4 us until the data was there, 1.5 us to put it into LDS and 2.2 - 3.4 us
+// of tiles, one after the other). Tiles never share an LDS slot, so one barrier per stage is all
+// the synchronisation there is; two waves per SIMD cover each other's stalls; the key parts are
+// merged through LDS (log-sum-exp, like the combine kernel does for the splits). Split partials
+// and final rows leave as in the streaming kernels, so the combine kernel and the workspace
+// layout are shared.
 #include <type_traits>
 
 #include "attn_mfma_common.h"
@@ -27,27 +32,30 @@ namespace {
 constexpr int kResWaves = 8;
 constexpr int kResMaxTiles = kResidentMaxKeys / kTileKeys; // 32-key tiles of one split
 
-template <int D, int NRB>
+template <int D, int NRB, int NT>
 __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(const AttnParams p) {
     constexpr int KS = D / 16;          // k-steps of the S^T product
     constexpr int DB = D / 32;          // 32-channel blocks of the output
     constexpr int KQ = kResWaves / NRB; // key parts inside the workgroup
+    constexpr int PPM = (NT + KQ - 1) / KQ; // tiles per key part = stages
     constexpr int SUB = kTileKeys * D;  // elements per 32-key tile of K (or V)
     constexpr int BPS = SUB * 2 / 1024; // 1 KB copy blocks per tile
     constexpr int LPR = D / 8;          // lanes (16-byte chunks) per row
     constexpr int RPI = 64 / LPR;       // rows per load instruction
-    constexpr int TPW = kResMaxTiles * BPS / kResWaves; // copy blocks per wave and tensor
-    static_assert(kResMaxTiles * BPS % kResWaves == 0, "copy blocks divide over the waves");
+    constexpr int SPW = (KQ * BPS + kResWaves - 1) / kResWaves; // copy blocks per wave, stage and tensor
     constexpr int MERGE_FLOATS = 64 * (DB * 16 + 2); // what a wave hands to the merge: accumulators, max, sum
-    static_assert((KQ - 1) * NRB * MERGE_FLOATS * 4 <= 2 * kResMaxTiles * SUB * 2, "merge area fits in the tile area");
+    constexpr int TILE_BYTES = 2 * NT * SUB * 2;
+    constexpr int MERGE_BYTES = (KQ - 1) * NRB * MERGE_FLOATS * 4;
+    constexpr int SMEM_ELEMS = (TILE_BYTES > MERGE_BYTES ? TILE_BYTES : MERGE_BYTES) / 2;
+    static_assert(NT >= 1 && NT <= kResMaxTiles, "a split holds at most kResidentMaxKeys keys");
 
-    // tiles: K[t] at smem + t*SUB, V[t] at smem + (kResMaxTiles + t)*SUB; after the last tile has
-    // been consumed the same memory carries the key parts' results to the merging waves
-    __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * kResMaxTiles * SUB];
+    // tiles: K[t] at smem + t*SUB, V[t] at smem + (NT + t)*SUB; after the last tile has been
+    // consumed the same memory carries the key parts' results to the merging waves
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[SMEM_ELEMS];
     __shared__ int32_t sp[VS_MAX_TREE];
     __shared__ int32_t sflag;
     uint16_t* sK = smem;
-    uint16_t* sV = smem + kResMaxTiles * SUB;
+    uint16_t* sV = smem + NT * SUB;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -57,27 +65,31 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
     const int rbw = wave % NRB; // row block inside the group
     const int kq = wave / NRB;  // key part
 
-    // workgroup id -> (sequence, KV head, split, row group); same XCD-aware remap as the other kernels
+    // workgroup id -> (sequence, KV head, row group, split); same XCD-aware remap as the other kernels
     const int per_xcd = (p.total_wgs + 7) >> 3;
     const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (v >= p.total_wgs) return;
-    const int rg = v % p.row_groups;
-    int rest = v / p.row_groups;
-    const int split = rest % p.num_splits;
-    rest /= p.num_splits;
+    // splits fastest: all key splits of a (sequence, KV head, row group) run on one XCD, whose L2
+    // then holds every partial result that the combine workgroups of those rows - placed on the
+    // same XCD by the same remap - are going to read
+    const int split = v % p.num_splits;
+    int rest = v / p.num_splits;
+    const int rg = rest % p.row_groups;
+    rest /= p.row_groups;
     const int kvh = rest % p.Hkv;
     const int b = rest / p.Hkv;
 
     const int32_t S = p.prefix_len[b]; // requested first, needed last: everything below is issued before it arrives
 
-    // ---- copy the split's keys and values: copy block i = tile i / BPS, rows RPI * (i % BPS) ..;
-    // wave w takes blocks w, w + 8, ...; one load instruction reads RPI whole rows (1 KB of
-    // consecutive memory). The loads do not wait for the prefix length: they are clamped to
-    // the cache (not to the sequence), and rows that turn out to lie past the sequence's last
-    // key are zeroed on their way into LDS (whatever the cache holds there - NaN included -
-    // must not meet a zero probability in the V product). A block-table entry outside the pool
-    // reads block 0. Chunk c of tile row r lands where the fragment reads expect it (same
-    // placement as the streaming kernel):
+    // ---- copy the split's keys and values. Stage j = tile j of every key part (tile kq * PPM + j);
+    // inside a stage, copy block i = (key part i / BPS, rows RPI * (i % BPS) ..) and wave w takes
+    // blocks w, w + 8, ...; one load instruction reads RPI whole rows (1 KB of consecutive memory).
+    // The loads do not wait for the prefix length: they are clamped to the cache (not to the
+    // sequence), and rows that turn out to lie past the sequence's last key are zeroed on their
+    // way into LDS (whatever the cache holds there - NaN included - must not meet a zero
+    // probability in the V product). A block-table entry outside the pool reads block 0. Chunk c
+    // of tile row r lands where the fragment reads expect it (same placement as the streaming
+    // kernel):
     //   K: ((r/16)*DB + c/4) * 1024 + (c%4) * 256 + ((r%16) ^ 4*(c%4)) * 16
     //   V: ((r/16)*DB + c/4) * 1024 + (4*(r%16) + c%4) * 16
     // (No branch around a block's loads or stores: a conditional assignment of the staging
@@ -91,23 +103,36 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
     const int k0 = split * p.keys_per_split; // the host keeps k0 below max_prefix_len + tree_keys, hence inside the cache
     const int64_t cache_tokens = p.paged ? (int64_t)p.max_blocks * p.block_size : p.capacity;
     const int kend = (int)(cache_tokens < (int64_t)k0 + p.keys_per_split ? cache_tokens : (int64_t)k0 + p.keys_per_split);
-    u32x4 kreg[TPW], vreg[TPW];
+    u32x4 kreg[PPM][SPW], vreg[PPM][SPW];
+    // tile and first row (inside the tile) of this wave's u-th copy block of stage j; blocks past the
+    // stage's last one (KQ * BPS not a multiple of the wave count) repeat its last block
+    auto block_tile = [&](int j, int u) __attribute__((always_inline)) {
+        const int i = min(wave + kResWaves * u, KQ * BPS - 1);
+        return min((i / BPS) * PPM + j, NT - 1);
+    };
+    auto block_row = [&](int u) __attribute__((always_inline)) {
+        const int i = min(wave + kResWaves * u, KQ * BPS - 1);
+        return (i % BPS) * RPI;
+    };
+    auto issue_stage = [&](auto is_v, int j) __attribute__((always_inline)) {
+        constexpr bool ISV = decltype(is_v)::value;
 #pragma unroll
-    for (int j = 0; j < TPW; ++j) {
-        const int i = wave + kResWaves * j; // copy block, uniform per wave
-        const int r0 = min(k0 + kTileKeys * (i / BPS) + RPI * (i % BPS), kend - 1); // RPI divides 16: one cache block in paged mode
-        int tok = min(r0 + lrow, kend - 1);
-        int64_t base = head_base;
-        if (p.paged) {
-            int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (r0 >> p.block_shift)];
-            if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
-            base += (int64_t)blk * p.stride_block;
-            tok &= p.block_size - 1;
+        for (int u = 0; u < SPW; ++u) {
+            const int r0 = min(k0 + kTileKeys * block_tile(j, u) + block_row(u), kend - 1); // RPI divides 16: one cache block in paged mode
+            int tok = min(r0 + lrow, kend - 1);
+            int64_t base = head_base;
+            if (p.paged) {
+                int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (r0 >> p.block_shift)];
+                if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
+                base += (int64_t)blk * p.stride_block;
+                tok &= p.block_size - 1;
+            }
+            const uint32_t off = (uint32_t)(tok * stride_tok + lchunk * 8);
+            if constexpr (ISV) vreg[j][u] = *(const u32x4*)(vbase + base + off);
+            else kreg[j][u] = *(const u32x4*)(kbase + base + off);
         }
-        const uint32_t off = (uint32_t)(tok * stride_tok + lchunk * 8);
-        kreg[j] = *(const u32x4*)(kbase + base + off);
-        vreg[j] = *(const u32x4*)(vbase + base + off);
-    }
+    };
+    issue_stage(std::false_type{}, 0); // the first keys lead: the first scores need them and the queries
 
     // ---- this wave's rows, mask and queries (in flight together with the tiles)
     const int row_base = rg * (NRB * kRowBlock) + rbw * kRowBlock;
@@ -121,6 +146,15 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qr + ks * 16));
     }
+    // the row's ancestor mask, when the caller supplies the masks: requested ahead of the later stages
+    uint64_t mask_given = 0;
+    if (p.tree_mask && p.tree_keys != 0) mask_given = p.tree_mask[(int64_t)b * p.T + node];
+    issue_stage(std::true_type{}, 0);
+#pragma unroll
+    for (int j = 1; j < PPM; ++j) {
+        issue_stage(std::false_type{}, j);
+        issue_stage(std::true_type{}, j);
+    }
 
     int32_t tree_code = VS_STATUS_OK;
     if (p.tree_mask || p.tree_keys == 0) {
@@ -129,7 +163,7 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
     } else {
         tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
     }
-    const uint64_t mask = p.tree_keys == 0 ? 0ull : (p.tree_mask ? p.tree_mask[(int64_t)b * p.T + node] : (tree_code == VS_STATUS_OK ? ancestor_mask(sp, node) : 0ull));
+    const uint64_t mask = p.tree_keys == 0 ? 0ull : (p.tree_mask ? mask_given : (tree_code == VS_STATUS_OK ? ancestor_mask(sp, node) : 0ull));
     const bool s_ok = prefix_ok(p, S);
     if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
     if (tree_code != VS_STATUS_OK || !s_ok) return;
@@ -139,23 +173,7 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
     const int k1 = min(nk, k0 + p.keys_per_split);
     const int nt = (k1 - k0 + kTileKeys - 1) / kTileKeys; // tiles of this split, <= kResMaxTiles
 
-#pragma unroll
-    for (int j = 0; j < TPW; ++j) {
-        const int i = wave + kResWaves * j; // < kResMaxTiles * BPS: always inside the tile area
-        const int t = i / BPS, rr = (i % BPS) * RPI + lrow, c = lchunk;
-        const bool live = k0 + kTileKeys * t + rr < k1;
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        const uint32_t ko = (uint32_t)(((rr >> 4) * DB + (c >> 2)) * 1024 + (c & 3) * 256 + (((rr & 15) ^ (4 * (c & 3))) * 16));
-        const uint32_t vo = (uint32_t)(((rr >> 4) * DB + (c >> 2)) * 1024 + (4 * (rr & 15) + (c & 3)) * 16);
-        *(u32x4*)((char*)(sK + t * SUB) + ko) = live ? kreg[j] : zero;
-        *(u32x4*)((char*)(sV + t * SUB) + vo) = live ? vreg[j] : zero;
-    }
-    __syncthreads();
-
-    // ---- this wave's key part: tiles [t_begin, t_end)
-    const int per_part = (nt + KQ - 1) / KQ;
-    const int t_begin = min(nt, kq * per_part), t_end = min(nt, t_begin + per_part);
-
+    // ---- this wave's key part: tiles kq * PPM + j, j = 0 .. PPM - 1 (those below nt)
     float m2 = -INFINITY, lsum = 0.f; // running reference (log2 domain, scaled) and this lane's share of the sum
     f32x16 acc[DB];
 #pragma unroll
@@ -241,15 +259,30 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[sl], acc[db], 0, 0, 0);
             }
     };
-    if (wave_active) {
-        // tiles that end at or before min(S, k1) hold prefix keys only
-        const int n_plain = max(0, min(S, k1) - k0) / kTileKeys;
-        int t = t_begin;
-        const int t_plain = min(t_end, n_plain);
-#pragma clang loop unroll(disable)
-        for (; t < t_plain; ++t) tile(std::false_type{}, t);
-#pragma clang loop unroll(disable)
-        for (; t < t_end; ++t) tile(std::true_type{}, t);
+    // tiles that end at or before min(S, k1) hold prefix keys only
+    const int n_plain = max(0, min(S, k1) - k0) / kTileKeys;
+#pragma unroll
+    for (int j = 0; j < PPM; ++j) {
+        // stage j has arrived once at most the later stages' loads are outstanding (loads return in
+        // order; the compiler counts them and waits for exactly that before the first use below)
+#pragma unroll
+        for (int u = 0; u < SPW; ++u) {
+            if (SPW * kResWaves == KQ * BPS || wave + kResWaves * u < KQ * BPS) { // uniform per wave
+                const int t = block_tile(j, u), rr = block_row(u) + lrow, c = lchunk;
+                const bool live = k0 + kTileKeys * t + rr < k1;
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                const uint32_t ko = (uint32_t)(((rr >> 4) * DB + (c >> 2)) * 1024 + (c & 3) * 256 + (((rr & 15) ^ (4 * (c & 3))) * 16));
+                const uint32_t vo = (uint32_t)(((rr >> 4) * DB + (c >> 2)) * 1024 + (4 * (rr & 15) + (c & 3)) * 16);
+                *(u32x4*)((char*)(sK + t * SUB) + ko) = live ? kreg[j][u] : zero;
+                *(u32x4*)((char*)(sV + t * SUB) + vo) = live ? vreg[j][u] : zero;
+            }
+        }
+        __syncthreads();
+        const int t = kq * PPM + j;
+        if (wave_active && t < nt) {
+            if (t < n_plain) tile(std::false_type{}, t);
+            else tile(std::true_type{}, t);
+        }
     }
 
     // ---- merge the key parts: parts 1.. hand (accumulators, reference, sum) to part 0 through LDS
@@ -315,11 +348,20 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
     }
 }
 
-template <int D, int NRB>
+template <int D, int NRB, int NT>
 hipError_t launch_res(const AttnParams& p, hipStream_t s) {
     const dim3 grid(((p.total_wgs + 7) / 8) * 8);
-    hipLaunchKernelGGL((attn_mfma_resident_kernel<D, NRB>), grid, dim3(kResWaves * kWave), 0, s, p);
+    hipLaunchKernelGGL((attn_mfma_resident_kernel<D, NRB, NT>), grid, dim3(kResWaves * kWave), 0, s, p);
     return hipGetLastError();
+}
+
+// NT = tiles per split (2, 4 or 6 tiles of 32 keys)
+template <int D, int NRB>
+hipError_t launch_res_nt(const AttnParams& p, hipStream_t s) {
+    const int nt = p.keys_per_split / kTileKeys;
+    if (nt <= 2) return launch_res<D, NRB, 2>(p, s);
+    if (nt <= 4) return launch_res<D, NRB, 4>(p, s);
+    return launch_res<D, NRB, 6>(p, s);
 }
 
 } // namespace
@@ -328,12 +370,12 @@ hipError_t launch_res(const AttnParams& p, hipStream_t s) {
 bool attention_resident_supported(int row_blocks) { return row_blocks == 4 || row_blocks == 2 || row_blocks == 1; }
 
 hipError_t launch_attention_mfma_resident(const AttnParams& p, int row_blocks, hipStream_t s) {
-    if (!attention_resident_supported(row_blocks) || p.keys_per_split > kResidentMaxKeys) return hipErrorInvalidValue;
+    if (!attention_resident_supported(row_blocks) || p.keys_per_split > kResidentMaxKeys || p.keys_per_split % kIterKeys) return hipErrorInvalidValue;
     if (p.d == 128) {
-        return row_blocks == 4 ? launch_res<128, 4>(p, s) : (row_blocks == 2 ? launch_res<128, 2>(p, s) : launch_res<128, 1>(p, s));
+        return row_blocks == 4 ? launch_res_nt<128, 4>(p, s) : (row_blocks == 2 ? launch_res_nt<128, 2>(p, s) : launch_res_nt<128, 1>(p, s));
     }
     if (p.d == 64) {
-        return row_blocks == 4 ? launch_res<64, 4>(p, s) : (row_blocks == 2 ? launch_res<64, 2>(p, s) : launch_res<64, 1>(p, s));
+        return row_blocks == 4 ? launch_res_nt<64, 4>(p, s) : (row_blocks == 2 ? launch_res_nt<64, 2>(p, s) : launch_res_nt<64, 1>(p, s));
     }
     return hipErrorInvalidValue;
 }

@@ -25,7 +25,8 @@ constexpr int kRowBlock = 32;   // query rows per MFMA row block
 constexpr int kMaxWaves = 8;    // waves per workgroup in the MFMA attention kernel
 constexpr int kArgmaxBlock = 256;
 constexpr int kAcceptChunk = 4096; // floats of a logits row per workgroup of the scans: 256 threads x 4 x 16 bytes
-constexpr int kResidentMaxKeys = 256; // keys of one split that the resident attention kernel keeps in LDS
+constexpr int kResidentMaxKeys = 192; // keys of one split that the resident attention kernel keeps in LDS (six 32-key tiles:
+                                      // with eight, its four-row-block form runs out of registers)
 
 // Everything the attention kernels need, passed by value.
 struct AttnParams {

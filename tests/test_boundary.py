@@ -21,6 +21,18 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert hasattr(L, name), name
     assert vs.vs_version() == 100
+    # the measurement helpers' header
+    hdr = open(os.path.join(ROOT, "include", "vispec_peaks.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(vs_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(vs.PEAK_SYMBOLS)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["vispec_peaks.h", "vispec_verify.h"]
+    g = 4096
+    assert vs.vs_peak_hbm_read(None, 1 << 20, g, 256) == -1 and vs.vs_peak_hbm_read(g + 4, 1 << 20, g, 256) == -2
+    assert vs.vs_peak_hbm_copy(g, g, 8, 256) == -2 and vs.vs_peak_mfma_bf16(g, 0, g, 256) == -2
+    assert vs.vs_peak_mfma_flops(10, 256) == 8 * 256 * 10 * 16 * 32768
 
 
 def test_error_strings():
@@ -84,11 +96,11 @@ def test_attention_descriptor_validation(kw, code):
 
 
 def test_plan_and_workspace_sizes():
-    # one layer of one short sequence: LDS-resident splits of 192 keys, four row blocks per workgroup
+    # one layer of one short sequence: LDS-resident splits of 128 keys, four row blocks per workgroup
     rc, plan = vs.vs_attention_plan(_desc())
     assert rc == 0 and plan.impl == vs.VS_IMPL_MFMA and plan.schedule == vs.VS_SCHED_RESIDENT
     assert plan.rows_per_wave == 1 and plan.waves_per_group == 8 and plan.row_groups == 4
-    assert plan.keys_per_split == 192 and plan.num_splits == 10
+    assert plan.keys_per_split == 128 and plan.num_splits == 14
     assert plan.workgroups == 4 * plan.row_groups * plan.num_splits and plan.combine == 1
     ws = vs.vs_attention_workspace_bytes(_desc())
     assert ws >= 4 * plan.num_splits * 448 * (128 * 2 + 2 * 4)          # bf16 partial rows + fp32 (max, sum)
@@ -111,10 +123,10 @@ def test_plan_and_workspace_sizes():
     assert three.schedule == vs.VS_SCHED_PIPELINED and three.waves_per_group == 8 and three.workgroups <= 256
     rc, one_mha = vs.vs_attention_plan(_desc(Hq=32, Hkv=32, stride_seq=32 * 1800 * 128))
     assert one_mha.schedule == vs.VS_SCHED_PIPELINED and one_mha.waves_per_group == 4 and one_mha.workgroups <= 256
-    # an explicit resident schedule caps a split at 256 keys whatever split count is asked for
+    # an explicit resident schedule caps a split at 192 keys whatever split count is asked for
     rc, pr = vs.vs_attention_plan(_desc(schedule=vs.VS_SCHED_RESIDENT, num_splits=1, max_prefix_len=6684, capacity=6800,
                                         stride_head=6800 * 128))
-    assert pr.keys_per_split == 256 and pr.num_splits == 27
+    assert pr.keys_per_split == 192 and pr.num_splits == 36
     # many units: pipelined kernel, eight waves, rows split over two workgroups, no key split, no combine
     big = _desc(B=28, stride_seq=4 * 1800 * 128)
     rc, pb = vs.vs_attention_plan(big)

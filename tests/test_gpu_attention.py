@@ -72,10 +72,10 @@ def test_full_size_single_sequence(gu, oracle_mod, name):
             got_p, _, dp = _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=sp, waves_per_group=nw,
                                           schedule=vs.VS_SCHED_PIPELINED)
             assert dp.plan().schedule == vs.VS_SCHED_PIPELINED
-    # the LDS-resident schedule: planner's split count (three 64-key tiles each), splits of one, two and four tiles
+    # the LDS-resident schedule: planner's split count (three 64-key tiles each), splits of one, two and three (the most) 64-key tiles
     for sp in (0, 10 ** 6, (inp.cfg.prefix[0] + inp.cfg.T + 127) // 128, 1):
         _, _, dr = _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=sp, schedule=vs.VS_SCHED_RESIDENT)
-        assert dr.plan().schedule == vs.VS_SCHED_RESIDENT and dr.plan().keys_per_split <= 256
+        assert dr.plan().schedule == vs.VS_SCHED_RESIDENT and dr.plan().keys_per_split <= 192
     _run_and_check(gu, oracle_mod, inp, ref=ref, impl=vs.VS_IMPL_GENERIC)
 
 
