@@ -46,7 +46,7 @@ def parse():
     return ap.parse_args()
 
 
-def other_config_leg(vs, gen, torch, dev, stream, gtorch, name, seed, check, oracle_depths=None):
+def other_config_leg(vs, gen, torch, dev, stream, gtorch, name, seed, check, num_splits=0, schedule=0):
     """Attention of one of the other configurations on device-generated data; returns a roofline block.
     C2 / C4: the L layers folded into one launch (contiguous caches); C5: one layer of the ragged batch
     over a paged cache with a shuffled block table."""
@@ -92,7 +92,7 @@ def other_config_leg(vs, gen, torch, dev, stream, gtorch, name, seed, check, ora
             v=torch.randn(kv_shape, generator=gtorch, device=dev, dtype=torch.float32).to(torch.bfloat16),
             out=torch.empty((B, T, Hq, d), device=dev, dtype=torch.bfloat16)))
     desc = vs.AttnDesc(B=B, T=T, Hq=Hq, Hkv=Hkv, d=d, dtype=vs.VS_BF16, softmax_scale=float(scale),
-                       max_prefix_len=int(S_b.max()), impl=vs.VS_IMPL_AUTO)
+                       max_prefix_len=int(S_b.max()), impl=vs.VS_IMPL_AUTO, num_splits=num_splits, schedule=schedule)
     if cfg.paged:
         desc.paged, desc.block_size, desc.max_blocks, desc.num_blocks = 1, bs, max_blocks, n_blocks
         desc.stride_block, desc.stride_head, desc.stride_tok = Hkv * bs * d, bs * d, d
@@ -486,7 +486,7 @@ def main():
         for name in ("C2", "C4", "C5"):
             if name == args.config:
                 continue
-            others[name] = other_config_leg(vs, gen, torch, dev, stream, gtorch, name, args.seed, check, oracle_depths=None)
+            others[name] = other_config_leg(vs, gen, torch, dev, stream, gtorch, name, args.seed, check)
 
     # ---------------------------------------------------------------- algorithmic work
     _, _, depth_h = oracle.tree_mask(parent_h[0])

@@ -35,7 +35,7 @@ namespace vs {
 
 namespace {
 
-template <int D, int RPW, int NW>
+template <int D, int RPW, int NW, bool PAGED>
 __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnParams p) {
     constexpr int KS = D / 16;                 // k-steps of the S^T product
     constexpr int DB = D / 32;                 // 32-channel blocks of the output
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     static_assert(BPS * RPI == kTileKeys, "a tile is BPS blocks of RPI rows");
     const uint16_t* kbase = (const uint16_t*)p.k;
     const uint16_t* vbase = (const uint16_t*)p.v;
-    const int64_t head_base = (p.paged ? 0 : (int64_t)b * p.stride_seq) + (int64_t)kvh * p.stride_head;
+    const int64_t head_base = (PAGED ? 0 : (int64_t)b * p.stride_seq) + (int64_t)kvh * p.stride_head;
     const int stride_tok = (int)p.stride_tok; // host guarantees 32-bit lane offsets
     const int lrow = lane / LPR, lchunk = lane % LPR;
     const uint32_t lane_off = (uint32_t)(lrow * stride_tok + lchunk * 8) * 2u; // bytes
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // turn out to lie past the sequence's last key are zeroed when the tiles go into LDS
     // (whatever the cache holds there, NaN included, must not meet a zero probability).
     {
-        const int64_t cache_tokens = p.paged ? (int64_t)p.max_blocks * p.block_size : p.capacity;
+        const int64_t cache_tokens = PAGED ? (int64_t)p.max_blocks * p.block_size : p.capacity;
         const int kend = (int)(cache_tokens < (int64_t)k0 + p.keys_per_split ? cache_tokens : (int64_t)k0 + p.keys_per_split);
         auto load_tile_early = [&](auto is_v, int t, u32x4(&r)[BPW]) __attribute__((always_inline)) {
             const uint16_t* gbase = decltype(is_v)::value ? vbase : kbase;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
                     const int r0 = min(k0 + t * kTileKeys + RPI * i, kend - 1); // RPI divides 16: one cache block in paged mode
                     int tok = min(r0 + lrow, kend - 1);
                     int64_t base = head_base;
-                    if (p.paged) {
+                    if (PAGED) {
                         int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (r0 >> p.block_shift)];
                         if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
                         base += (int64_t)blk * p.stride_block;
@@ -168,6 +168,33 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     const char* vfast = (const char*)(vbase + head_base + (int64_t)k0 * stride_tok);
     // LFAST: contiguous cache and a full tile, so the address is a wave-uniform base plus a
     // per-lane constant and nothing needs clamping.
+    // Paged caches: the block ids of the tiles to come sit one per lane in two registers (a window of
+    // 128 consecutive table entries, fetched with two coalesced loads and moved along as the tiles
+    // advance), so a tile copy gets its block id with v_readlane instead of a scalar load per copy -
+    // whose result the copy would have to wait for, together with every LDS read in flight (scalar
+    // loads and LDS share one wait counter).
+    const int32_t* bt_row = PAGED ? p.block_table + (int64_t)b * p.max_blocks : nullptr;
+    int bt_base = k0 >> p.block_shift; // logical block of lane 0 of the first window register
+    int32_t bt_win0 = 0, bt_win1 = 0;
+    auto bt_fetch = [&](int first) __attribute__((always_inline)) { return bt_row[min(first + lane, p.max_blocks - 1)]; };
+    if (PAGED) {
+        bt_win0 = bt_fetch(bt_base);
+        bt_win1 = bt_fetch(bt_base + 64);
+    }
+    // moves the window so that it starts at or before logical block `lb_min` (called once per iteration)
+    auto bt_advance = [&](int lb_min) __attribute__((always_inline)) {
+        if (PAGED && lb_min >= bt_base + 64) { // uniform
+            bt_base += 64;
+            bt_win0 = bt_win1;
+            bt_win1 = bt_fetch(bt_base + 64);
+        }
+    };
+    auto bt_lookup = [&](int lb) __attribute__((always_inline)) {
+        const int rel = lb - bt_base; // 0 .. 127 by construction
+        int32_t blk = rel < 64 ? __builtin_amdgcn_readlane(bt_win0, rel & 63) : __builtin_amdgcn_readlane(bt_win1, rel & 63);
+        if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
+        return blk;
+    };
     auto load_tile = [&](auto lfast_tag, auto is_v, int t, u32x4(&r)[BPW]) __attribute__((always_inline)) {
         constexpr bool LFAST = decltype(lfast_tag)::value;
         constexpr bool ISV = decltype(is_v)::value;
@@ -190,10 +217,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
                     const int r0 = k0 + t * kTileKeys + RPI * i; // RPI divides 16: one cache block in paged mode
                     int tok = min(r0 + lrow, k1 - 1);
                     int64_t base = head_base;
-                    if (p.paged) {
-                        int32_t blk = p.block_table[(int64_t)b * p.max_blocks + (min(r0, k1 - 1) >> p.block_shift)];
-                        if ((uint32_t)blk >= (uint32_t)p.num_blocks) blk = 0; // reported through status
-                        base += (int64_t)blk * p.stride_block;
+                    if (PAGED) {
+                        base += (int64_t)bt_lookup(min(r0, k1 - 1) >> p.block_shift) * p.stride_block;
                         tok &= p.block_size - 1;
                     }
                     const uint32_t off = (uint32_t)(tok * stride_tok + lchunk * 8);
@@ -531,6 +556,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
         using masked_t = std::integral_constant<bool, !FAST>;
         const int tb = ta + 1;
         const int g = ta >> 1;
+        // this iteration requests group g + 2 = tiles 2g + 5 .. 2g + 8
+        bt_advance(min(k0 + (2 * g + 5) * kTileKeys, k1 - 1) >> p.block_shift);
         // first tile: S(tb), O(ta - 1) | P(ta)
         if (wave_active) {
             float alpha[RPW];
@@ -586,7 +613,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // of the range last), so three loops in a row cover every case. Iteration ta loads
     // group ta/2 + 2 = tiles up to ta + 8.
     int ta = 0;
-    if (!p.paged)
+    if constexpr (!PAGED)
         for (; ta + 2 < fast_end && ta + 10 < n_full; ta += 4) {
             iteration(T{}, T{}, S0{}, ta);
             iteration(T{}, T{}, S1{}, ta + 2);
@@ -645,7 +672,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
 template <int D, int RPW, int NW>
 hipError_t launch_pipe(const AttnParams& p, hipStream_t s) {
     const dim3 grid(((p.total_wgs + 7) / 8) * 8);
-    hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW>), grid, dim3(NW * kWave), 0, s, p);
+    if (p.paged) hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW, true>), grid, dim3(NW * kWave), 0, s, p);
+    else hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW, false>), grid, dim3(NW * kWave), 0, s, p);
     return hipGetLastError();
 }
 
