@@ -516,6 +516,7 @@ def main():
         roofline["traffic"] = traffic.get(args.config, {}).get("folded_attention_call_bytes")
         roofline["traffic_source"] = "profiles/hbm_traffic.json: " + traffic.get("_source", "rocprofv3 --pmc runs of this command")
     except OSError:
+        traffic = {}
         roofline["traffic_source"] = "not measured"
     def kernel_name(pl):
         k = {vs.VS_SCHED_PIPELINED: "attn_mfma_pipe_kernel", vs.VS_SCHED_RESIDENT: "attn_mfma_resident_kernel"}.get(
@@ -535,6 +536,8 @@ def main():
     per_layer.update({"launch": "one layer, B=1: the call the timed step issues once per layer", "us_per_launch": round(ms_single * 1e3, 2),
                       "workgroups": plan1.workgroups, "num_splits": plan1.num_splits, "kernel": kernel_name(plan1),
                       "algorithmic_bytes": int(bytes_layer), "workspace_bytes": int(vs.vs_attention_workspace_bytes(desc1))})
+    per_layer["traffic"] = traffic.get(args.config, {}).get("per_layer_call_bytes")
+    per_layer["traffic_source"] = roofline["traffic_source"]
     for blk in (roofline, per_layer):
         blk["frac_of_measured_mfma_random"] = round(blk["achieved"] / measured_peaks["mfma_bf16_random_tflops"], 4) if bound == "mfma" else None
     argmax_gbs = logit_bytes / (ms_accept * 1e-3) / 1e9

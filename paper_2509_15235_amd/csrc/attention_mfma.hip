@@ -92,10 +92,11 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
     // Workgroup id -> (sequence, KV head, row group, split). Consecutive hardware ids go
     // round-robin over the 8 XCDs; the remap gives every XCD a contiguous range of work, so the
     // workgroups of one (sequence, KV head) share an XCD's L2 for their K/V as far as they fit,
-    // and - splits being the fastest index - all key splits of a row group run on one XCD, whose
-    // L2 then holds the partial results that the combine workgroups of those rows (placed by the
-    // same remap) read. Measured on one C3 layer: 19.0 -> 16.7 us per call against an order with
-    // the row groups fastest, whose partials came from two XCDs.
+    // and - splits being the fastest index - all key splits of a row group run on one XCD: the
+    // combine workgroups of those rows, placed by the same remap, then read a slice of the
+    // workspace that only this XCD has touched. Measured on one C3 layer (10 splits): 19.0 us per
+    // call with row groups fastest and the combine grid in natural order, 16.7 us with both
+    // kernels laid out this way; with only one of the two changed 19.4 (main) / 17.2 (combine).
     const int per_xcd = (p.total_wgs + 7) >> 3;
     const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (v >= p.total_wgs) return;
@@ -490,9 +491,13 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
     constexpr int DB = D / 32;
     __shared__ __attribute__((aligned(16))) uint16_t so[kRowBlock][32 + 8];
     // Workgroup id -> (unit, row group, row block of the group, channel block), in contiguous ranges
-    // per XCD like the main kernels: the partials of a row group's splits were written through the L2
-    // of the XCD that ran them, and with splits as the main kernel's fastest index (resident schedule)
-    // that is the XCD these rows' combine workgroups land on.
+    // per XCD like the main kernels: with splits as the main kernels' fastest index, the partials of
+    // a row group were all written by one XCD, and that is the XCD these rows' combine workgroups
+    // land on. Every XCD then stays on its own eighth of the workspace in both kernels and from one
+    // call to the next (2.3 us per one-layer call against a grid whose neighbouring workgroups -
+    // on eight different XCDs - read neighbouring pieces of the same partial blocks; the counters
+    // show the partials still arrive from memory, not from L2, so what is saved is address
+    // translation and fabric traffic rather than the fetch itself).
     const int rbg = p.rows_per_group / kRowBlock; // row blocks per row group
     const int items = p.B * p.Hkv * p.row_groups * rbg * DB;
     const int per_xcd = (items + 7) >> 3;

@@ -69,9 +69,8 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
     const int per_xcd = (p.total_wgs + 7) >> 3;
     const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (v >= p.total_wgs) return;
-    // splits fastest: all key splits of a (sequence, KV head, row group) run on one XCD, whose L2
-    // then holds every partial result that the combine workgroups of those rows - placed on the
-    // same XCD by the same remap - are going to read
+    // splits fastest: all key splits of a (sequence, KV head, row group) run on one XCD, the one
+    // that the combine workgroups of those rows are placed on by the same remap (see attention_mfma.hip)
     const int split = v % p.num_splits;
     int rest = v / p.num_splits;
     const int rg = rest % p.row_groups;
