@@ -459,14 +459,10 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
         } else {
             if (row_base + rb * kRowBlock >= p.rows) continue; // whole block is padding
             const int64_t blk = part_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
-            uint16_t* po = p.part_o + blk * (kRowBlock * D) + lane * 4;
+            uint16_t* po = p.part_o + blk * (kRowBlock * D);
             const float inv = l > 0.f ? 1.f / l : 0.f; // no visible key in this split: zeros, weight 0
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4)
-                    *(u32x2*)(po + (db * 4 + q4) * 256) = pack_partial(acc[rb][db][4 * q4], acc[rb][db][4 * q4 + 1],
-                                                                      acc[rb][db][4 * q4 + 2], acc[rb][db][4 * q4 + 3], inv);
+            for (int db = 0; db < DB; ++db) store_partial<D>(po, db, lane, acc[rb][db], inv);
             if (half == 0) {
                 const f32x2 ml = {m2[rb], l};
                 const int64_t mlb = ml_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
@@ -514,7 +510,7 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
     const f32x2* gml = (const f32x2*)p.part_ml + ml_block(p, unit, 0, rbk) + col; // + s * kRowBlock
     const int64_t blk0 = part_block(p, unit, 0, rbk);
     const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
-    const uint16_t* po0 = p.part_o + blk0 * (kRowBlock * D) + (db * 4) * 256 + lane * 4;
+    const uint16_t* po0 = p.part_o + blk0 * (kRowBlock * D) + ((db * 2) * 64 + lane) * 8;
 
     float den = 0.f, M = -INFINITY;
     f32x4 num[4];
@@ -523,7 +519,7 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
     int nsplit = 0;
     for (int s0 = 0; s0 < p.num_splits; s0 += kCombineBatch) {
         f32x2 ml[kCombineBatch];
-        u32x2 o[kCombineBatch][4];
+        u32x4 o[kCombineBatch][2];
 #pragma unroll
         for (int u = 0; u < kCombineBatch; ++u)
             if (s0 + u < p.num_splits) ml[u] = __builtin_nontemporal_load(gml + (s0 + u) * kRowBlock);
@@ -532,7 +528,7 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
             if (s0 + u < p.num_splits) {
                 const uint16_t* po = po0 + (s0 + u) * blk_stride * (kRowBlock * D);
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) o[u][q4] = __builtin_nontemporal_load((const u32x2*)(po + q4 * 256));
+                for (int hp = 0; hp < 2; ++hp) o[u][hp] = __builtin_nontemporal_load((const u32x4*)(po + hp * 512));
             }
         if (s0 == 0) {
             if (!prefix_ok(p, S)) return;
@@ -556,7 +552,10 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
                 const float w = (ml[u][0] != -INFINITY) ? __builtin_amdgcn_exp2f(ml[u][0] - M) * ml[u][1] : 0.f;
                 den += w;
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) num[q4] += w * unpack_partial(o[u][q4]);
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const u32x2 piece = {o[u][q4 >> 1][2 * (q4 & 1)], o[u][q4 >> 1][2 * (q4 & 1) + 1]};
+                    num[q4] += w * unpack_partial(piece);
+                }
             }
     }
     const float inv = 1.f / den;

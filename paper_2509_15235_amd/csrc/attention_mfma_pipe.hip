@@ -652,14 +652,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
         } else {
             if (row_base + rb * kRowBlock >= p.rows) continue; // whole block is padding
             const int64_t blk = part_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
-            uint16_t* po = p.part_o + blk * (kRowBlock * D) + lane * 4;
+            uint16_t* po = p.part_o + blk * (kRowBlock * D);
             const float inv = l > 0.f ? 1.f / l : 0.f; // no visible key in this split: zeros, weight 0
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4)
-                    *(u32x2*)(po + (db * 4 + q4) * 256) = pack_partial(acc[rb][db][4 * q4], acc[rb][db][4 * q4 + 1],
-                                                                      acc[rb][db][4 * q4 + 2], acc[rb][db][4 * q4 + 3], inv);
+            for (int db = 0; db < DB; ++db) store_partial<D>(po, db, lane, acc[rb][db], inv);
             if (half == 0) {
                 const f32x2 ml = {m2[rb], l};
                 const int64_t mlb = ml_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);

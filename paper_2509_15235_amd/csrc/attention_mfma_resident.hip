@@ -43,9 +43,8 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
     constexpr int LPR = D / 8;          // lanes (16-byte chunks) per row
     constexpr int RPI = 64 / LPR;       // rows per load instruction
     constexpr int SPW = (KQ * BPS + kResWaves - 1) / kResWaves; // copy blocks per wave, stage and tensor
-    constexpr int MERGE_FLOATS = 64 * (DB * 16 + 2); // what a wave hands to the merge: accumulators, max, sum
     constexpr int TILE_BYTES = 2 * NT * SUB * 2;
-    constexpr int MERGE_BYTES = (KQ - 1) * NRB * MERGE_FLOATS * 4;
+    constexpr int MERGE_BYTES = kResWaves * (DB * 1024 + 128) * 4; // every wave's exchange area: accumulators, max, sum
     constexpr int SMEM_ELEMS = (TILE_BYTES > MERGE_BYTES ? TILE_BYTES : MERGE_BYTES) / 2;
     static_assert(NT >= 1 && NT <= kResMaxTiles, "a split holds at most kResidentMaxKeys keys");
 
@@ -284,66 +283,122 @@ __global__ __launch_bounds__(kResWaves * 64, 2) void attn_mfma_resident_kernel(c
         }
     }
 
-    // ---- merge the key parts: parts 1.. hand (accumulators, reference, sum) to part 0 through LDS
+    // ---- merge the key parts through LDS (log-sum-exp) and write the rows. The work is shared: a row
+    // block's accumulators are 2 * DB pieces of eight registers (piece = channel block * 2 + half of
+    // its registers, the 16-byte unit of the partial-result layout); key part k owns pieces
+    // k * PPK .. (k + 1) * PPK - 1, receives the other parts' versions of those, merges them in ascending
+    // part order (so every wave of a row block computes the same sum) and stores them. Every wave
+    // hands (8 - PPK pieces, max, sum) over and takes as much back, instead of part 0 doing all of it.
     __syncthreads(); // every wave is done with the tiles
     float* sm = (float*)smem;
-    if (kq > 0 && wave_active) {
-        float* dst = sm + ((kq - 1) * NRB + rbw) * MERGE_FLOATS + lane;
+    constexpr int NP = 2 * DB;                    // pieces per row block
+    constexpr int PPK = NP / KQ > 0 ? NP / KQ : 1; // pieces owned by a key part
+    constexpr int OWNERS = NP / PPK;              // key parts that own pieces (all of them unless KQ > NP)
+    constexpr int XCH = NP * 512 + 128;           // floats a wave's exchange area holds: pieces [piece][2][64 lanes][4], max[64], sum[64]
+    static_assert(kResWaves * XCH * 4 <= SMEM_ELEMS * 2, "exchange area fits");
+    float* mine = sm + (rbw * KQ + kq) * XCH;
+    auto piece_owner = [](int pc) { return pc / PPK; };
+    if (wave_active) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int pc = 0; pc < NP; ++pc) {
+            // written by everybody but the owner; which pieces those are depends on kq, the registers
+            // they come from do not
+            if (piece_owner(pc) != kq) {
+                const int db = pc >> 1, hp = pc & 1;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) dst[(db * 16 + q) * 64] = acc[db][q];
-        dst[(DB * 16) * 64] = m2;
-        dst[(DB * 16 + 1) * 64] = lsum;
+                for (int hh = 0; hh < 2; ++hh) {
+                    const f32x4 w = {acc[db][8 * hp + 4 * hh], acc[db][8 * hp + 4 * hh + 1], acc[db][8 * hp + 4 * hh + 2],
+                                     acc[db][8 * hp + 4 * hh + 3]};
+                    *(f32x4*)(mine + pc * 512 + hh * 256 + lane * 4) = w;
+                }
+            }
+        }
+        mine[NP * 512 + lane] = m2;
+        mine[NP * 512 + 64 + lane] = lsum;
     }
     __syncthreads();
-    if (kq > 0 || !wave_active) return;
-#pragma unroll
-    for (int o = 1; o < KQ; ++o) {
-        const float* src = sm + ((o - 1) * NRB + rbw) * MERGE_FLOATS + lane;
-        const float mo = src[(DB * 16) * 64], lo = src[(DB * 16 + 1) * 64];
-        const float M = fmaxf(m2, mo);
-        if (M == -INFINITY) continue; // neither part has seen a visible key
-        const float fa = __builtin_amdgcn_exp2f(m2 - M), fb = __builtin_amdgcn_exp2f(mo - M); // exp2(-inf) = 0
-        lsum = lsum * fa + lo * fb;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) acc[db][q] = acc[db][q] * fa + src[(db * 16 + q) * 64] * fb;
-        m2 = M;
-    }
+    if (!wave_active || kq >= OWNERS) return;
 
-    // ---- epilogue: lane (col, half) holds, for row `col`, channels db*32 + 8*(q/4) + 4*half + q%4
+    // reference and sum over all key parts, the same arithmetic in every wave of the row block
+    float mo[KQ], lo[KQ];
+#pragma unroll
+    for (int o = 0; o < KQ; ++o) {
+        const float* src = sm + (rbw * KQ + o) * XCH;
+        mo[o] = src[NP * 512 + lane];
+        lo[o] = src[NP * 512 + 64 + lane];
+    }
+    float M = mo[0];
+#pragma unroll
+    for (int o = 1; o < KQ; ++o) M = fmaxf(M, mo[o]);
+    const float Ms = (M == -INFINITY) ? 0.f : M; // no part has seen a visible key: every factor below is 2^-inf = 0
+    float fo[KQ], lall = 0.f;
+#pragma unroll
+    for (int o = 0; o < KQ; ++o) {
+        fo[o] = __builtin_amdgcn_exp2f(mo[o] - Ms);
+        lall += lo[o] * fo[o];
+    }
+    const float l = half_sum(lall);
     const int r_local = row_base + col;
-    const float l = half_sum(lsum);
-    if (p.num_splits == 1) {
-        if (r_local >= p.rows) return;
-        uint16_t* o = (uint16_t*)p.out + (((int64_t)b * p.T + node) * p.Hq + hq) * D;
-        const float inv = 1.f / l;
+    const bool final_rows = p.num_splits == 1;
+    const float inv = final_rows ? 1.f / l : (l > 0.f ? 1.f / l : 0.f); // partials: no visible key in this split -> zeros, weight 0
+    uint16_t* orow = (uint16_t*)p.out + (((int64_t)b * p.T + node) * p.Hq + hq) * D;
+    uint16_t* po = p.part_o + part_block(p, (int64_t)b * p.Hkv + kvh, split, row_base >> 5) * (kRowBlock * D);
+
+    // this wave's pieces: lane (col, half) holds, for row `col`, channels db*32 + 8*(q/4) + 4*half + q%4
+    auto finish = [&](auto kq_tag) __attribute__((always_inline)) {
+        constexpr int MY = decltype(kq_tag)::value;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int i = 0; i < PPK; ++i) {
+            const int pc = MY * PPK + i, db = pc >> 1, hp = pc & 1;
+            float r[8];
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                u32x2 w;
-                w[0] = pack_bf16x2(acc[db][4 * q4] * inv, acc[db][4 * q4 + 1] * inv);
-                w[1] = pack_bf16x2(acc[db][4 * q4 + 2] * inv, acc[db][4 * q4 + 3] * inv);
-                *(u32x2*)(o + db * 32 + 8 * q4 + 4 * half) = w;
+            for (int e = 0; e < 8; ++e) r[e] = 0.f;
+#pragma unroll
+            for (int o = 0; o < KQ; ++o) {
+                if (o == MY) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) r[e] += fo[o] * acc[db][8 * hp + e];
+                } else {
+                    const float* src = sm + (rbw * KQ + o) * XCH + pc * 512 + lane * 4;
+                    const f32x4 a0 = *(const f32x4*)src, a1 = *(const f32x4*)(src + 256);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        r[e] += fo[o] * a0[e];
+                        r[4 + e] += fo[o] * a1[e];
+                    }
+                }
             }
-    } else {
-        const int64_t blk = part_block(p, (int64_t)b * p.Hkv + kvh, split, row_base >> 5);
-        uint16_t* po = p.part_o + blk * (kRowBlock * D) + lane * 4;
-        const float inv = l > 0.f ? 1.f / l : 0.f; // no visible key in this split: zeros, weight 0
+            if (final_rows) {
+                if (r_local < p.rows) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                *(u32x2*)(po + (db * 4 + q4) * 256) = pack_partial(acc[db][4 * q4], acc[db][4 * q4 + 1], acc[db][4 * q4 + 2],
-                                                                  acc[db][4 * q4 + 3], inv);
-        if (half == 0) {
-            const f32x2 ml = {m2, l};
-            const int64_t mlb = ml_block(p, (int64_t)b * p.Hkv + kvh, split, row_base >> 5);
-            *(f32x2*)(p.part_ml + (mlb + col) * 2) = ml;
+                    for (int hh = 0; hh < 2; ++hh) {
+                        u32x2 w;
+                        w[0] = pack_bf16x2(r[4 * hh] * inv, r[4 * hh + 1] * inv);
+                        w[1] = pack_bf16x2(r[4 * hh + 2] * inv, r[4 * hh + 3] * inv);
+                        *(u32x2*)(orow + db * 32 + 8 * (2 * hp + hh) + 4 * half) = w;
+                    }
+                }
+            } else {
+                const u32x2 w0 = pack_partial(r[0], r[1], r[2], r[3], inv), w1 = pack_partial(r[4], r[5], r[6], r[7], inv);
+                const u32x4 w = {w0[0], w0[1], w1[0], w1[1]};
+                *(u32x4*)(po + (pc * 64 + lane) * 8) = w;
+            }
         }
+    };
+    switch (kq) { // uniform per wave; the case fixes which registers are this wave's
+    case 0: finish(std::integral_constant<int, 0>{}); break;
+    case 1: finish(std::integral_constant<int, 1 % OWNERS>{}); break;
+    case 2: finish(std::integral_constant<int, 2 % OWNERS>{}); break;
+    case 3: finish(std::integral_constant<int, 3 % OWNERS>{}); break;
+    case 4: finish(std::integral_constant<int, 4 % OWNERS>{}); break;
+    case 5: finish(std::integral_constant<int, 5 % OWNERS>{}); break;
+    case 6: finish(std::integral_constant<int, 6 % OWNERS>{}); break;
+    default: finish(std::integral_constant<int, 7 % OWNERS>{}); break;
+    }
+    if (!final_rows && kq == 0 && half == 0) {
+        const f32x2 ml = {M, l};
+        const int64_t mlb = ml_block(p, (int64_t)b * p.Hkv + kvh, split, row_base >> 5);
+        *(f32x2*)(p.part_ml + (mlb + col) * 2) = ml;
     }
 }
 

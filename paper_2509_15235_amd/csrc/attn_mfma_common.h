@@ -35,8 +35,10 @@ __device__ __forceinline__ float half_sum(float x) {
 }
 
 // Partial results of one (sequence, KV head, split, 32-row block): D/32 accumulator blocks,
-// each stored as 4 x [64 lanes x 4 values] (register r = 4*q4 + e of lane l at
-// ((db*4 + q4)*64 + l)*4 + e), followed elsewhere by 32 x (max, sum) in fp32. A partial output
+// each stored as 2 x [64 lanes x 8 values] (register r = 4*q4 + e of lane l at
+// ((db*2 + q4/2)*64 + l)*8 + (q4%2)*4 + e: a lane's eight values are one 16-byte piece, a wave's
+// store or load of a piece is 1 KB of consecutive memory), followed elsewhere by 32 x (max, sum)
+// in fp32. A partial output
 // row is divided by its own sum before it is rounded: a convex combination of V rows, as large
 // as the largest visible |V| and no larger. It is stored as bf16, which has V's own exponent
 // range (fp16 would turn any |v| > 65504 into infinity) and costs half the bytes of fp32: what a
@@ -54,6 +56,18 @@ __device__ __forceinline__ f32x4 unpack_partial(u32x2 w) {
     const f32x4 r = {__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xffff0000u), __uint_as_float(w[1] << 16),
                      __uint_as_float(w[1] & 0xffff0000u)};
     return r;
+}
+// One 32-channel accumulator block of a row block, divided by the rows' sums: two 16-byte pieces per
+// lane. `blk` = start of the (unit, split, row block) partial block, db = channel block.
+template <int D>
+__device__ __forceinline__ void store_partial(uint16_t* blk, int db, int lane, const f32x16& a, float inv) {
+#pragma unroll
+    for (int hp = 0; hp < 2; ++hp) {
+        const u32x2 lo = pack_partial(a[8 * hp], a[8 * hp + 1], a[8 * hp + 2], a[8 * hp + 3], inv);
+        const u32x2 hi = pack_partial(a[8 * hp + 4], a[8 * hp + 5], a[8 * hp + 6], a[8 * hp + 7], inv);
+        const u32x4 w = {lo[0], lo[1], hi[0], hi[1]};
+        *(u32x4*)(blk + ((db * 2 + hp) * 64 + lane) * 8) = w;
+    }
 }
 __device__ __forceinline__ int64_t part_block(const AttnParams& p, int64_t unit, int split, int rbk) {
     return (unit * p.num_splits + split) * (int64_t)(p.rows_pad / kRowBlock) + rbk;
