@@ -142,7 +142,8 @@ def other_config_leg(vs, gen, torch, dev, stream, gtorch, name, seed, check, num
         blk.update({"achieved": round(tf, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)})
     else:
         blk.update({"achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)})
-    sched = {vs.VS_SCHED_PIPELINED: "attn_mfma_pipe_kernel", vs.VS_SCHED_RESIDENT: "attn_mfma_resident_kernel"}.get(plan.schedule, "attn_mfma_kernel")
+    sched = {vs.VS_SCHED_PIPELINED: "attn_mfma_pipe_kernel", vs.VS_SCHED_BALANCED: "attn_mfma_pipe_kernel (balanced shares)",
+             vs.VS_SCHED_RESIDENT: "attn_mfma_resident_kernel"}.get(plan.schedule, "attn_mfma_kernel")
     blk.update({"traffic": None, "workload": cfg.name, "launch": launch, "us_per_launch": round(ms * 1e3, 2),
                 "tflops": round(tf, 2), "hbm_gbs": round(gbs, 1), "workgroups": plan.workgroups, "num_splits": plan.num_splits,
                 "kernel": sched + (" + attn_combine_kernel" if plan.combine else ""),

@@ -84,13 +84,19 @@ typedef enum vs_attn_impl { VS_IMPL_AUTO = 0, VS_IMPL_GENERIC = 1, VS_IMPL_MFMA 
  * three stages (scores, softmax, output update) back to back; PIPELINED overlaps the matrix-core
  * work of the neighbouring tiles with the current tile's softmax (launches with many units);
  * RESIDENT keeps a split's whole key range (at most 192 keys) in LDS and splits the
- * keys once more among the waves of a workgroup (latency-bound launches with few units).
+ * keys once more among the waves of a workgroup (latency-bound launches with few units);
+ * BALANCED is the pipelined kernel on a batch whose sequences differ in length: the kernels read
+ * the prefix lengths, lay all sequences' keys end to end and give every workgroup an equal share
+ * of them (a share may end one sequence and begin the next), instead of cutting every sequence
+ * into the same number of splits sized for the longest allowed one (at most 64 sequences; bf16;
+ * `num_splits`, if not 0, is the number of shares per KV head and row group, at most 64).
  * Same results up to fp32 rounding. AUTO chooses from the shape. */
 typedef enum vs_attn_schedule {
     VS_SCHED_AUTO = 0,
     VS_SCHED_LOOP = 1,
     VS_SCHED_PIPELINED = 2,
-    VS_SCHED_RESIDENT = 3
+    VS_SCHED_RESIDENT = 3,
+    VS_SCHED_BALANCED = 4
 } vs_attn_schedule;
 
 int32_t vs_version(void);
@@ -162,14 +168,14 @@ typedef struct vs_attn_desc {
 /* What a call with this descriptor would launch (for tests and reports). */
 typedef struct vs_attn_plan {
     int32_t impl;            /* VS_IMPL_GENERIC or VS_IMPL_MFMA */
-    int32_t num_splits;      /* upper bound on key splits per (sequence, KV head) */
-    int32_t keys_per_split;
+    int32_t num_splits;      /* upper bound on key splits per (sequence, KV head); BALANCED: shares per (KV head, row group) */
+    int32_t keys_per_split;  /* BALANCED: 0, the shares are sized from the prefix lengths at run time */
     int32_t row_groups;      /* workgroups that share one (sequence, KV head, split) */
     int32_t waves_per_group;
     int32_t rows_per_wave;   /* 32-row blocks per wave (MFMA path) */
     int32_t workgroups;      /* main kernel grid size */
     int32_t combine;         /* 1 if a split-combine kernel follows */
-    int32_t schedule;        /* VS_SCHED_LOOP, VS_SCHED_PIPELINED or VS_SCHED_RESIDENT (MFMA path), else 0 */
+    int32_t schedule;        /* VS_SCHED_LOOP, _PIPELINED, _RESIDENT or _BALANCED (MFMA path), else 0 */
 } vs_attn_plan;
 
 int32_t vs_attention_plan(const vs_attn_desc* desc, vs_attn_plan* plan); /* both host */

@@ -8,7 +8,7 @@ functions raises.
 """
 from .binding import (  # noqa: F401
     AttnDesc, AttnPlan, KVDesc, VSError, lib, lib_path,
-    VS_BF16, VS_F32, VS_IMPL_AUTO, VS_IMPL_GENERIC, VS_IMPL_MFMA, VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED, VS_SCHED_RESIDENT,
+    VS_BF16, VS_F32, VS_IMPL_AUTO, VS_IMPL_GENERIC, VS_IMPL_MFMA, VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED, VS_SCHED_RESIDENT, VS_SCHED_BALANCED,
     vs_version, vs_strerror, vs_status_string, vs_tree_validate_host, vs_tree_mask_build,
     vs_attention_plan, vs_attention_workspace_bytes, vs_tree_verify_attention,
     vs_accept_workspace_bytes, vs_tree_accept, vs_tree_accept_noalloc, vs_accept_sample_workspace_bytes, vs_tree_accept_sample,

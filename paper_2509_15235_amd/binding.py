@@ -11,7 +11,7 @@ _LIB_PATH = os.environ.get("VISPEC_VERIFY_LIB") or os.path.join(_HERE, "libvispe
 
 VS_BF16, VS_F32 = 0, 1
 VS_IMPL_AUTO, VS_IMPL_GENERIC, VS_IMPL_MFMA = 0, 1, 2
-VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED, VS_SCHED_RESIDENT = 0, 1, 2, 3
+VS_SCHED_AUTO, VS_SCHED_LOOP, VS_SCHED_PIPELINED, VS_SCHED_RESIDENT, VS_SCHED_BALANCED = 0, 1, 2, 3, 4
 
 EXPORTED_SYMBOLS = [
     "vs_version", "vs_strerror", "vs_status_string", "vs_tree_validate_host", "vs_tree_mask_build",

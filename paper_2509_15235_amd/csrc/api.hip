@@ -48,6 +48,7 @@ namespace {
 
 struct Plan {
     int32_t impl, rpw, waves, row_groups, rows, rows_pad, num_splits, keys_per_split, total_wgs, schedule;
+    int32_t bal_chunks; // balanced schedule: shares per (KV head, row group); num_splits = slots per KV head
     int32_t res_rb; // resident schedule: row blocks per workgroup (4, 2 or 1)
 };
 
@@ -68,11 +69,16 @@ int32_t check_desc(const vs_attn_desc* d, int tree = 1) {
         d->waves_per_group != 8)
         return VS_ERR_SHAPE;
     if (d->schedule != VS_SCHED_AUTO && d->schedule != VS_SCHED_LOOP && d->schedule != VS_SCHED_PIPELINED &&
-        d->schedule != VS_SCHED_RESIDENT)
+        d->schedule != VS_SCHED_RESIDENT && d->schedule != VS_SCHED_BALANCED)
         return VS_ERR_SHAPE;
     if (d->schedule == VS_SCHED_RESIDENT && (d->rows_per_wave == 2 || (d->waves_per_group != 0 && d->waves_per_group != 8)))
         return VS_ERR_SHAPE; // eight waves, one row block each
-    if (d->schedule == VS_SCHED_PIPELINED) {
+    if (d->schedule == VS_SCHED_BALANCED) {
+        // a lane per sequence and per share; num_splits, when given, is the number of shares
+        if (d->B > kBalMaxSeqs || d->num_splits > kBalMaxChunks) return VS_ERR_SHAPE;
+        if (d->impl == VS_IMPL_GENERIC || d->dtype != VS_BF16) return VS_ERR_SHAPE;
+    }
+    if (d->schedule == VS_SCHED_PIPELINED || d->schedule == VS_SCHED_BALANCED) {
         // the pipelined kernel exists for one row block per wave and four or eight waves
         if (d->rows_per_wave == 2) return VS_ERR_SHAPE;
         if (d->waves_per_group != 0 && d->waves_per_group != 4 && d->waves_per_group != 8) return VS_ERR_SHAPE;
@@ -152,10 +158,33 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     // layer): A/B per call, loop against pipelined, 3 sequences 26.3 / 24.9 us, 4: 28.6 / 26.9,
     // 6: 34.0 / 29.7, 8: 39.9 / 31.4, 11: 50.9 / 39.9, one C2 (MHA) layer 25.4 / 23.3; below
     // that the loop wins (one C3 sequence 19.1 / 22.5, two 21.7 / 23.3).
+    // Balanced shares instead of equal splits per sequence: for batches whose sequences may differ in
+    // length (the host only knows the longest allowed one), when the launch needs key splits to fill
+    // the CUs at all and a share would be 32 steps of 64 keys if every sequence had that length
+    // (reading the lengths and cutting the shares costs each kernel a dependent load and a few
+    // microseconds: paged batches of 16 Qwen-7B-shaped sequences, equal splits against balanced shares,
+    // lengths drawn from 1024 .. 8192: 138 / 120, 135 / 109, 138 / 106, 127 / 99 us; all 4600: 93 / 100;
+    // all 8000: 150 / 156; drawn from 256 .. 2048: 50 / 57).
+    const int bal_waves = waves ? waves : (nrb > 4 ? 8 : 4);
+    const int bal_rg = (nrb + bal_waves - 1) / bal_waves;
+    const int bal_w_auto = kNumCUs / (d->Hkv * bal_rg) > kBalMaxChunks ? kBalMaxChunks : kNumCUs / (d->Hkv * bal_rg);
+    const bool balanced_ok = many && pipe_ok && splits <= 0 && d->B >= 2 && d->B <= kBalMaxSeqs && units0 * bal_rg < 200 &&
+                             bal_w_auto >= 2 && (int64_t)d->B * tiles >= 32 * (int64_t)bal_w_auto;
     pl.schedule = d->schedule != VS_SCHED_AUTO ? d->schedule
+                  : balanced_ok                ? VS_SCHED_BALANCED
                   : many && pipe_ok            ? VS_SCHED_PIPELINED
                   : resident_ok                ? VS_SCHED_RESIDENT
                                                : VS_SCHED_LOOP;
+    if (pl.schedule == VS_SCHED_BALANCED) {
+        pl.rpw = 1;
+        pl.waves = bal_waves;
+        pl.row_groups = bal_rg;
+        pl.bal_chunks = splits > 0 ? splits : (bal_w_auto < 1 ? 1 : bal_w_auto);
+        pl.num_splits = pl.bal_chunks + d->B; // partial-result slots per KV head
+        pl.keys_per_split = 0;                // shares are measured at run time
+        pl.total_wgs = pl.bal_chunks * d->Hkv * pl.row_groups;
+        return pl;
+    }
     if (pl.schedule == VS_SCHED_RESIDENT) {
         // eight waves = res_rb row blocks x 8 / res_rb key parts; a split holds at most
         // kResidentMaxKeys keys (three 64-key tiles)
@@ -225,10 +254,17 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     return pl;
 }
 
+// rows of partial results: every (sequence, KV head) has num_splits slots; the balanced schedule has
+// num_splits slots per KV head for the whole batch
+size_t partial_rows(const vs_attn_desc* d, const Plan& pl) {
+    return (size_t)(pl.bal_chunks > 0 ? 1 : d->B) * d->Hkv * pl.num_splits * pl.rows_pad;
+}
+
 size_t workspace_bytes(const vs_attn_desc* d, const Plan& pl) {
     if (pl.impl != VS_IMPL_MFMA || pl.num_splits <= 1) return 0;
-    const size_t prow = (size_t)d->B * d->Hkv * pl.num_splits * pl.rows_pad;
-    return align_up(prow * d->d * sizeof(uint16_t)) + align_up(prow * 2 * sizeof(float));
+    const size_t prow = partial_rows(d, pl);
+    return align_up(prow * d->d * sizeof(uint16_t)) + align_up(prow * 2 * sizeof(float)) +
+           (pl.bal_chunks > 0 ? align_up(kBalMaxChunks * sizeof(int32_t)) : 0);
 }
 
 constexpr int kArgmaxChunk = kAcceptChunk;
@@ -289,7 +325,7 @@ int32_t vs_attention_plan(const vs_attn_desc* desc, vs_attn_plan* plan) {
     if (rc != VS_OK) return rc;
     const Plan pl = make_plan(desc);
     plan->impl = pl.impl;
-    plan->num_splits = pl.num_splits;
+    plan->num_splits = pl.bal_chunks > 0 ? pl.bal_chunks : pl.num_splits;
     plan->keys_per_split = pl.keys_per_split;
     plan->row_groups = pl.row_groups;
     plan->waves_per_group = pl.waves;
@@ -359,17 +395,19 @@ int32_t enqueue_attention(const vs_attn_desc* desc, int tree, const void* q, con
     p.row_groups = pl.row_groups;
     p.rows_per_group = (pl.schedule == VS_SCHED_RESIDENT ? pl.res_rb : pl.waves * pl.rpw) * kRowBlock;
     p.total_wgs = pl.total_wgs;
+    p.bal_chunks = pl.bal_chunks;
     if (need > 0) {
-        const size_t prow = (size_t)desc->B * desc->Hkv * pl.num_splits * pl.rows_pad;
+        const size_t prow = partial_rows(desc, pl);
         p.part_o = (uint16_t*)workspace;
         p.part_ml = (float*)((char*)workspace + align_up(prow * desc->d * sizeof(uint16_t)));
+        if (pl.bal_chunks > 0) p.bal_table = (int32_t*)((char*)p.part_ml + align_up(prow * 2 * sizeof(float)));
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     if (pl.impl == VS_IMPL_GENERIC) {
         e = launch_attention_generic(p, desc->dtype, s);
     } else {
-        e = pl.schedule == VS_SCHED_PIPELINED ? launch_attention_mfma_pipe(p, pl.rpw, pl.waves, s)
+        e = (pl.schedule == VS_SCHED_PIPELINED || pl.schedule == VS_SCHED_BALANCED) ? launch_attention_mfma_pipe(p, pl.rpw, pl.waves, s)
             : pl.schedule == VS_SCHED_RESIDENT ? launch_attention_mfma_resident(p, pl.res_rb, s)
                                                : launch_attention_mfma(p, pl.rpw, pl.waves, s);
         if (e == hipSuccess && pl.num_splits > 1) e = launch_attention_combine(p, desc->dtype, s);

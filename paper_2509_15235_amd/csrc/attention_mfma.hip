@@ -482,10 +482,11 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnParams p) 
 // bytes; they are loaded but never used). A sequence whose prefix length is out of range
 // is skipped; a malformed tree (reported by the main kernel) leaves unspecified output.
 constexpr int kCombineBatch = 16; // splits whose partials are in flight together
-template <int D>
+template <int D, bool BAL>
 __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p) {
     constexpr int DB = D / 32;
     __shared__ __attribute__((aligned(16))) uint16_t so[kRowBlock][32 + 8];
+    __shared__ int32_t sslot[BAL ? kBalMaxChunks : 1]; // balanced schedule: the slots of this sequence's pieces
     // Workgroup id -> (unit, row group, row block of the group, channel block), in contiguous ranges
     // per XCD like the main kernels: with splits as the main kernels' fastest index, the partials of
     // a row group were all written by one XCD, and that is the XCD these rows' combine workgroups
@@ -506,10 +507,11 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
     if (rbk * kRowBlock >= p.rows) return; // padding of the last row group
     const int b = unit / p.Hkv, kvh = unit % p.Hkv;
     const int lane = threadIdx.x, col = lane & 31, half = lane >> 5;
-    const int32_t S = p.prefix_len[b];
-    const f32x2* gml = (const f32x2*)p.part_ml + ml_block(p, unit, 0, rbk) + col; // + s * kRowBlock
-    const int64_t blk0 = part_block(p, unit, 0, rbk);
-    const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per split
+    const int32_t S = BAL ? 0 : p.prefix_len[b];
+    const int64_t punit = BAL ? kvh : unit; // whose partial-result slots these are
+    const f32x2* gml = (const f32x2*)p.part_ml + ml_block(p, punit, 0, rbk) + col; // + slot * kRowBlock
+    const int64_t blk0 = part_block(p, punit, 0, rbk);
+    const int64_t blk_stride = p.rows_pad / kRowBlock; // blocks per slot
     const uint16_t* po0 = p.part_o + blk0 * (kRowBlock * D) + ((db * 2) * 64 + lane) * 8;
 
     float den = 0.f, M = -INFINITY;
@@ -517,20 +519,40 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) num[q4] = f32x4{0.f, 0.f, 0.f, 0.f};
     int nsplit = 0;
-    for (int s0 = 0; s0 < p.num_splits; s0 += kCombineBatch) {
+    int nload = p.num_splits; // partials requested (splits past the sequence's end included: they are not used)
+    if constexpr (BAL) {
+        // the shares that hold keys of this sequence, found the way the main kernel found them
+        int start, steps, total;
+        bool usable;
+        bal_scan(p, lane, start, steps, total, usable);
+        const int bounds = p.bal_table[lane];
+        const int up = __shfl_down(bounds, 1);
+        const int hi = lane + 1 < p.bal_chunks ? up : total;
+        const int s0 = __builtin_amdgcn_readlane(start, b), t = __builtin_amdgcn_readlane(steps, b);
+        int t0, t1;
+        const bool mine = lane < p.bal_chunks && bal_piece(bounds, hi, s0, t, t0, t1);
+        const uint64_t m = __ballot(mine);
+        nsplit = __popcll(m);
+        if (nsplit <= 1) return; // no usable prefix, or a single piece: its rows are final already
+        if (mine) sslot[__popcll(m & ((1ull << lane) - 1ull))] = lane + b;
+        __syncthreads();
+        nload = nsplit;
+    }
+    auto slot_of = [&](int u) __attribute__((always_inline)) { return BAL ? sslot[u] : u; };
+    for (int s0 = 0; s0 < nload; s0 += kCombineBatch) {
         f32x2 ml[kCombineBatch];
         u32x4 o[kCombineBatch][2];
 #pragma unroll
         for (int u = 0; u < kCombineBatch; ++u)
-            if (s0 + u < p.num_splits) ml[u] = __builtin_nontemporal_load(gml + (s0 + u) * kRowBlock);
+            if (s0 + u < nload) ml[u] = __builtin_nontemporal_load(gml + slot_of(s0 + u) * kRowBlock);
 #pragma unroll
         for (int u = 0; u < kCombineBatch; ++u)
-            if (s0 + u < p.num_splits) {
-                const uint16_t* po = po0 + (s0 + u) * blk_stride * (kRowBlock * D);
+            if (s0 + u < nload) {
+                const uint16_t* po = po0 + slot_of(s0 + u) * blk_stride * (kRowBlock * D);
 #pragma unroll
                 for (int hp = 0; hp < 2; ++hp) o[u][hp] = __builtin_nontemporal_load((const u32x4*)(po + hp * 512));
             }
-        if (s0 == 0) {
+        if (!BAL && s0 == 0) {
             if (!prefix_ok(p, S)) return;
             nsplit = min(p.num_splits, (S + p.tree_keys + p.keys_per_split - 1) / p.keys_per_split);
         }
@@ -605,8 +627,12 @@ hipError_t launch_attention_combine(const AttnParams& p, int dtype, hipStream_t 
     (void)dtype;
     const int items = p.B * p.Hkv * p.row_groups * (p.rows_per_group / kRowBlock) * (p.d / 32);
     const dim3 grid((unsigned)((items + 7) / 8 * 8));
-    if (p.d == 128) hipLaunchKernelGGL((attn_combine_kernel<128>), grid, dim3(kWave), 0, s, p);
-    else if (p.d == 64) hipLaunchKernelGGL((attn_combine_kernel<64>), grid, dim3(kWave), 0, s, p);
+    if (p.bal_chunks > 0) {
+        if (p.d == 128) hipLaunchKernelGGL((attn_combine_kernel<128, true>), grid, dim3(kWave), 0, s, p);
+        else if (p.d == 64) hipLaunchKernelGGL((attn_combine_kernel<64, true>), grid, dim3(kWave), 0, s, p);
+        else return hipErrorInvalidValue;
+    } else if (p.d == 128) hipLaunchKernelGGL((attn_combine_kernel<128, false>), grid, dim3(kWave), 0, s, p);
+    else if (p.d == 64) hipLaunchKernelGGL((attn_combine_kernel<64, false>), grid, dim3(kWave), 0, s, p);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

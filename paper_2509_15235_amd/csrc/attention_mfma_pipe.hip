@@ -35,7 +35,7 @@ namespace vs {
 
 namespace {
 
-template <int D, int RPW, int NW, bool PAGED>
+template <int D, int RPW, int NW, bool PAGED, bool BAL>
 __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnParams p) {
     constexpr int KS = D / 16;                 // k-steps of the S^T product
     constexpr int DB = D / 32;                 // 32-channel blocks of the output
@@ -55,19 +55,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     const int half = lane >> 5;
     const int col = lane & 31;
 
-    // workgroup id -> (sequence, KV head, row group, split), XCD-aware (see attention_mfma.hip)
-    const int per_xcd = (p.total_wgs + 7) >> 3;
-    const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (v >= p.total_wgs) return;
-    const int split = v % p.num_splits; // splits fastest, see attention_mfma.hip
-    int rest = v / p.num_splits;
-    const int rg = rest % p.row_groups;
-    rest /= p.row_groups;
-    const int kvh = rest % p.Hkv;
-    const int b = rest / p.Hkv;
-
+    // One piece of work: the rows of row group `rg` of (sequence b, KV head kvh) against the keys
+    // [k0, k0 + klen) of that sequence (k0 lies inside the cache). `whole`: no other piece shares these
+    // rows, they leave as final output; else as the partial result of slot `slot`.
+    auto run_piece = [&](const int b, const int kvh, const int rg, const int k0, const int klen, const int slot,
+                         const bool whole) __attribute__((always_inline)) {
     const int32_t S = p.prefix_len[b]; // requested first, needed last: the first tiles and the queries are requested before it arrives
-    const int k0 = split * p.keys_per_split; // the host keeps k0 below max_prefix_len + tree_keys, hence inside the cache
 
     // ---- tile copies. One load instruction of a wave fetches 1 KB of consecutive memory:
     // RPI whole rows (tokens) of D channels, lane q -> row q / LPR, 16-byte chunk q % LPR, so
@@ -101,7 +94,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // (whatever the cache holds there, NaN included, must not meet a zero probability).
     {
         const int64_t cache_tokens = PAGED ? (int64_t)p.max_blocks * p.block_size : p.capacity;
-        const int kend = (int)(cache_tokens < (int64_t)k0 + p.keys_per_split ? cache_tokens : (int64_t)k0 + p.keys_per_split);
+        const int kend = (int)(cache_tokens < (int64_t)k0 + klen ? cache_tokens : (int64_t)k0 + klen);
         auto load_tile_early = [&](auto is_v, int t, u32x4(&r)[BPW]) __attribute__((always_inline)) {
             const uint16_t* gbase = decltype(is_v)::value ? vbase : kbase;
 #pragma unroll
@@ -154,12 +147,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
         tree_code = load_tree(p.parent + (int64_t)b * p.T, p.T, sp, &sflag);
     }
     const bool s_ok = prefix_ok(p, S);
-    if (kvh == 0 && split == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
+    if (kvh == 0 && k0 == 0 && rg == 0) report_status(p, b, tree_code, s_ok, S, &sflag);
     if (tree_code != VS_STATUS_OK || !s_ok) return;
 
     const int nk = S + p.tree_keys;
     if (k0 >= nk) return;
-    const int k1 = min(nk, k0 + p.keys_per_split);
+    const int k1 = min(nk, k0 + klen);
     const int n = (k1 - k0 + kTileKeys - 1) / kTileKeys; // tiles of this split
 
     const int n_full = (k1 - k0) / kTileKeys; // tiles without a ragged end
@@ -634,7 +627,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     for (int rb = 0; rb < RPW; ++rb) {
         const int r_local = row_base + rb * kRowBlock + col;
         const float l = half_sum(lsum[rb]);
-        if (p.num_splits == 1) {
+        if (whole) {
             if (r_local >= p.rows) continue;
             const int node = r_local / p.group;
             const int hq = kvh * p.group + (r_local - node * p.group);
@@ -651,15 +644,57 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
                 }
         } else {
             if (row_base + rb * kRowBlock >= p.rows) continue; // whole block is padding
-            const int64_t blk = part_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
+            const int64_t unit = BAL ? kvh : (int64_t)b * p.Hkv + kvh;
+            const int64_t blk = part_block(p, unit, slot, (row_base >> 5) + rb);
             uint16_t* po = p.part_o + blk * (kRowBlock * D);
             const float inv = l > 0.f ? 1.f / l : 0.f; // no visible key in this split: zeros, weight 0
 #pragma unroll
             for (int db = 0; db < DB; ++db) store_partial<D>(po, db, lane, acc[rb][db], inv);
             if (half == 0) {
                 const f32x2 ml = {m2[rb], l};
-                const int64_t mlb = ml_block(p, (int64_t)b * p.Hkv + kvh, split, (row_base >> 5) + rb);
+                const int64_t mlb = ml_block(p, unit, slot, (row_base >> 5) + rb);
                 *(f32x2*)(p.part_ml + (mlb + col) * 2) = ml;
+            }
+        }
+    }
+    }; // run_piece
+
+    if constexpr (!BAL) {
+        // workgroup id -> (sequence, KV head, row group, split), XCD-aware (see attention_mfma.hip)
+        const int per_xcd = (p.total_wgs + 7) >> 3;
+        const int v = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+        if (v >= p.total_wgs) return;
+        const int split = v % p.num_splits; // splits fastest, see attention_mfma.hip
+        int rest = v / p.num_splits;
+        const int rg = rest % p.row_groups;
+        rest /= p.row_groups;
+        const int kvh = rest % p.Hkv;
+        const int b = rest / p.Hkv;
+        // the host keeps every split's first key below max_prefix_len + tree_keys, hence inside the cache
+        run_piece(b, kvh, rg, split * p.keys_per_split, p.keys_per_split, split, p.num_splits == 1);
+    } else {
+        // workgroup id -> (share, KV head, row group): the row groups of a (share, KV head) sit next to each
+        // other on one XCD (they read the same keys), consecutive (share, KV head) pairs on different ones
+        const int xj = blockIdx.x >> 3;
+        const int rg = xj % p.row_groups;
+        const int u = (xj / p.row_groups) * 8 + (blockIdx.x & 7);
+        const int c = u / p.Hkv, kvh = u % p.Hkv;
+        if (c >= p.bal_chunks) return;
+        int start, steps, total;
+        bool usable;
+        bal_scan(p, lane, start, steps, total, usable);
+        // sequences that no piece will ever visit report their bad prefix length here
+        if (c == 0 && kvh == 0 && rg == 0 && wave == 0 && lane < p.B && !usable && p.status) p.status[lane] = VS_STATUS_BAD_PREFIX;
+        const int bounds = bal_bounds(p, lane, start, steps, total);
+        if (c == 0 && kvh == 0 && rg == 0 && wave == 0) p.bal_table[lane] = bounds; // for the combine kernel
+        const int lo = __builtin_amdgcn_readlane(bounds, c);
+        const int hi = c + 1 < p.bal_chunks ? __builtin_amdgcn_readlane(bounds, c + 1) : total;
+        for (int i = 0; i < p.B; ++i) {
+            const int s0 = __builtin_amdgcn_readlane(start, i), t = __builtin_amdgcn_readlane(steps, i);
+            int t0, t1;
+            if (bal_piece(lo, hi, s0, t, t0, t1)) { // uniform
+                __syncthreads(); // the previous piece's last reads of the tile rings, the tree and the flag
+                run_piece(i, kvh, rg, t0 * kIterKeys, (t1 - t0) * kIterKeys, c + i, t0 == 0 && t1 == t);
             }
         }
     }
@@ -667,9 +702,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
 
 template <int D, int RPW, int NW>
 hipError_t launch_pipe(const AttnParams& p, hipStream_t s) {
+    if (p.bal_chunks > 0) {
+        const dim3 grid(((p.bal_chunks * p.Hkv + 7) / 8) * 8 * p.row_groups);
+        if (p.paged) hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW, true, true>), grid, dim3(NW * kWave), 0, s, p);
+        else hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW, false, true>), grid, dim3(NW * kWave), 0, s, p);
+        return hipGetLastError();
+    }
     const dim3 grid(((p.total_wgs + 7) / 8) * 8);
-    if (p.paged) hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW, true>), grid, dim3(NW * kWave), 0, s, p);
-    else hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW, false>), grid, dim3(NW * kWave), 0, s, p);
+    if (p.paged) hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW, true, false>), grid, dim3(NW * kWave), 0, s, p);
+    else hipLaunchKernelGGL((attn_mfma_pipe_kernel<D, RPW, NW, false, false>), grid, dim3(NW * kWave), 0, s, p);
     return hipGetLastError();
 }
 

@@ -78,4 +78,101 @@ __device__ __forceinline__ int64_t ml_block(const AttnParams& p, int64_t unit, i
     return ((unit * (p.rows_pad / kRowBlock) + rbk) * p.num_splits + split) * (int64_t)kRowBlock;
 }
 
+// ---- Balanced schedule: the key ranges of a whole ragged batch, cut into shares of equal cost.
+// The keys of all sequences, counted in 64-key steps, are laid end to end (sequence 0 first); share c
+// of W covers steps [bound(c), bound(c + 1)) of that line, and the part of a sequence that falls
+// into a share is a piece of work: a share that crosses from one sequence into the next is worked
+// off piece by piece. A piece costs its steps plus kBalPieceCost (queries, first tiles, the
+// pipeline's fill and drain: what happens before a piece's first and after its last step takes about
+// as long as six steps). Lane i of a wave holds sequence i (at most 64 sequences). Main and combine
+// kernel both derive the shares from the prefix lengths with the routines below, so they agree on
+// where every piece's partial result lies: slot (share + sequence) of its KV head.
+constexpr int kBalPieceCost = 6;
+constexpr int kBalSnap = 3; // no piece this short (in steps) is left behind at a sequence's end
+
+// this lane's sequence: its first step on the line and its number of steps (0: not usable)
+__device__ __forceinline__ void bal_scan(const AttnParams& p, int lane, int& start, int& steps, int& total, bool& usable) {
+    const int32_t S = lane < p.B ? p.prefix_len[lane] : -1;
+    usable = lane < p.B && prefix_ok(p, S);
+    steps = usable ? (S + p.tree_keys + kIterKeys - 1) / kIterKeys : 0;
+    int inc = steps;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    start = inc - steps;
+    total = __builtin_amdgcn_readlane(inc, 63);
+}
+
+// the steps [a, b) of a sequence (first step s0, t steps) that fall into [lo, hi) of the line; false: none
+__device__ __forceinline__ bool bal_piece(int lo, int hi, int s0, int t, int& a, int& b) {
+    a = max(lo, s0) - s0;
+    b = min(hi, s0 + t) - s0;
+    return b > a;
+}
+
+// cost of the most expensive share under the boundaries held one per lane (lane c: first step of share c)
+__device__ __forceinline__ int bal_worst(const AttnParams& p, int lane, int start, int steps, int total, int bounds) {
+    const int up = __shfl_down(bounds, 1);
+    const int hi = lane + 1 < p.bal_chunks ? up : total;
+    int cost = 0;
+    for (int i = 0; i < p.B; ++i) {
+        int a, b;
+        if (bal_piece(bounds, hi, __builtin_amdgcn_readlane(start, i), __builtin_amdgcn_readlane(steps, i), a, b))
+            cost += kBalPieceCost + (b - a);
+    }
+    if (lane >= p.bal_chunks) cost = 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cost = max(cost, __shfl_xor(cost, o));
+    return cost;
+}
+
+// lane c (c < W): first step of share c; the other lanes: the end of the line.
+// Two cuts are priced (most expensive share, a piece costing its steps plus kBalPieceCost) and the
+// cheaper one is taken:
+//  * even: the line with kBalPieceCost units inserted in front of every sequence is divided into W
+//    equal parts; a boundary that falls into such a start-up stretch, or within kBalSnap steps of
+//    either end of a sequence, moves onto the sequence's boundary (no stubs);
+//  * regular, when W is a multiple of the number of sequences: every sequence gets W / B shares of
+//    ceil(longest sequence / (W / B)) steps - what equal splits per sequence would be. Batches of
+//    (nearly) equal lengths keep their equal splits this way.
+// All lanes work side by side (a lane per share, a uniform loop over the sequences): a serial fill,
+// share after share, costs a lone wave more than ten microseconds.
+__device__ __forceinline__ int bal_bounds(const AttnParams& p, int lane, int start, int steps, int total) {
+    const int W = p.bal_chunks;
+    const int nseq = __popcll(__ballot(steps > 0));
+    // start-up stretches in front of this lane's sequence: the usable sequences before it
+    const int before = __popcll(__ballot(steps > 0) & ((1ull << lane) - 1ull));
+    const int lstart = start + kBalPieceCost * before; // this lane's sequence on the stretched line
+    const int ltotal = total + kBalPieceCost * nseq;
+    const int raw = (int)((int64_t)min(lane, W) * ltotal / W);
+    const int snap = min(kBalSnap, ltotal / W / 4);
+    int even = lane < W ? -1 : total;
+    for (int i = 0; i < p.B; ++i) {
+        const int l0 = __builtin_amdgcn_readlane(lstart, i), s0 = __builtin_amdgcn_readlane(start, i);
+        const int t = __builtin_amdgcn_readlane(steps, i);
+        const int lend = l0 + kBalPieceCost + t;
+        if (t > 0 && l0 <= raw && raw < lend) {
+            if (raw - l0 <= kBalPieceCost + snap) even = s0;
+            else if (lend - raw <= snap) even = s0 + t;
+            else even = s0 + (raw - l0 - kBalPieceCost);
+        }
+    }
+    if (even < 0) even = total; // raw == ltotal only for lanes >= W; an empty batch has no stretch to fall into
+    int bounds = even;
+    if (W % p.B == 0) {
+        const int r = W / p.B;
+        int smax = steps;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) smax = max(smax, __shfl_xor(smax, o));
+        const int k = (smax + r - 1) / r;
+        const int b = min(lane / r, p.B - 1), j = lane % r;
+        const int sb = __shfl(start, b), tb = __shfl(steps, b);
+        const int regular = lane < W ? sb + min(j * k, tb) : total;
+        if (bal_worst(p, lane, start, steps, total, regular) <= bal_worst(p, lane, start, steps, total, even)) bounds = regular;
+    }
+    return bounds;
+}
+
 } // namespace vs

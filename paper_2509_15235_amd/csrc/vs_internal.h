@@ -25,6 +25,8 @@ constexpr int kRowBlock = 32;   // query rows per MFMA row block
 constexpr int kMaxWaves = 8;    // waves per workgroup in the MFMA attention kernel
 constexpr int kArgmaxBlock = 256;
 constexpr int kAcceptChunk = 4096; // floats of a logits row per workgroup of the scans: 256 threads x 4 x 16 bytes
+constexpr int kBalMaxSeqs = 64;   // balanced schedule: sequences per call (a lane each)
+constexpr int kBalMaxChunks = 64; // ... and shares per (KV head, row group)
 constexpr int kResidentMaxKeys = 192; // keys of one split that the resident attention kernel keeps in LDS (six 32-key tiles:
                                       // with eight, its four-row-block form runs out of registers)
 
@@ -57,6 +59,9 @@ struct AttnParams {
     int32_t row_groups;
     int32_t rows_per_group;     // waves_per_group * row blocks per wave * kRowBlock
     int32_t total_wgs;          // B * Hkv * num_splits * row_groups
+    int32_t* bal_table;         // balanced schedule: 64 words of workspace, the share boundaries (main kernel -> combine)
+    int32_t bal_chunks;         // balanced schedule: equal shares of the batch's keys per (KV head, row group); else 0.
+                                // num_splits then counts partial-result slots per KV head (shares + sequences)
 };
 
 struct AcceptParams {

@@ -82,7 +82,11 @@ def _desc(**kw):
     ({"paged": 1, "block_size": 24, "max_blocks": 200, "num_blocks": 300, "block_table": 4096}, -6),
     ({"paged": 1, "block_size": 16, "max_blocks": 10, "num_blocks": 300, "block_table": 4096}, -6),
     ({"num_splits": -1}, -2),
-    ({"schedule": 4}, -2), ({"schedule": vs.VS_SCHED_PIPELINED, "rows_per_wave": 2}, -2),
+    ({"schedule": 5}, -2), ({"schedule": vs.VS_SCHED_PIPELINED, "rows_per_wave": 2}, -2),
+    ({"schedule": vs.VS_SCHED_BALANCED}, 0), ({"schedule": vs.VS_SCHED_BALANCED, "num_splits": 64}, 0),
+    ({"schedule": vs.VS_SCHED_BALANCED, "num_splits": 65}, -2), ({"schedule": vs.VS_SCHED_BALANCED, "B": 65}, -2),
+    ({"schedule": vs.VS_SCHED_BALANCED, "rows_per_wave": 2}, -2), ({"schedule": vs.VS_SCHED_BALANCED, "waves_per_group": 2}, -2),
+    ({"schedule": vs.VS_SCHED_BALANCED, "impl": vs.VS_IMPL_GENERIC}, -2),
     ({"schedule": vs.VS_SCHED_RESIDENT}, 0), ({"schedule": vs.VS_SCHED_RESIDENT, "rows_per_wave": 2}, -2),
     ({"schedule": vs.VS_SCHED_RESIDENT, "waves_per_group": 4}, -2),
     ({"schedule": vs.VS_SCHED_PIPELINED, "waves_per_group": 2}, -2),
@@ -140,7 +144,18 @@ def test_plan_and_workspace_sizes():
     # fewer units than CUs: key splits fill the machine
     mid = _desc(B=16, max_prefix_len=8192, capacity=8300, stride_seq=4 * 8300 * 128, stride_head=8300 * 128)
     rc, pm5 = vs.vs_attention_plan(mid)
+    # ... by equal shares of the whole batch's keys, since the sequences of a batch may differ in length
+    assert pm5.schedule == vs.VS_SCHED_BALANCED and pm5.num_splits == 32 and pm5.keys_per_split == 0
+    assert pm5.workgroups == 256 and pm5.combine == 1 and pm5.waves_per_group == 8 and pm5.row_groups == 2
+    # 4 KV heads x (32 shares + 16 sequences) slots of 448 rows: bf16 rows plus (max, sum) pairs
+    assert vs.vs_attention_workspace_bytes(mid) == 4 * 48 * 448 * (128 * 2 + 8) + 256
+    mid.schedule = vs.VS_SCHED_PIPELINED
+    rc, pm5 = vs.vs_attention_plan(mid)
     assert pm5.schedule == vs.VS_SCHED_PIPELINED and pm5.num_splits == 2 and pm5.workgroups == 256 and pm5.combine == 1
+    # the caller's split count, short sequences, or a single sequence keep the equal splits
+    assert vs.vs_attention_plan(_desc(B=16, max_prefix_len=8192, capacity=8300, stride_seq=4 * 8300 * 128,
+                                      stride_head=8300 * 128, num_splits=3))[1].schedule == vs.VS_SCHED_PIPELINED
+    assert vs.vs_attention_plan(_desc(B=8, stride_seq=4 * 1800 * 128))[1].schedule == vs.VS_SCHED_PIPELINED
     # few row blocks per unit (MHA): four waves
     mha = _desc(B=32, Hq=32, Hkv=32, max_prefix_len=3136, capacity=3300, stride_seq=32 * 3300 * 128, stride_head=3300 * 128)
     rc, pm2 = vs.vs_attention_plan(mha)

@@ -68,7 +68,8 @@ def test_matches_oracle_every_kernel(gu, oracle_mod, nq, Hq, Hkv, lens):
     for impl, sched, splits, waves in ((vs.VS_IMPL_MFMA, vs.VS_SCHED_LOOP, 0, 0), (vs.VS_IMPL_MFMA, vs.VS_SCHED_LOOP, 1, 0),
                                        (vs.VS_IMPL_MFMA, vs.VS_SCHED_LOOP, 3, 8), (vs.VS_IMPL_MFMA, vs.VS_SCHED_PIPELINED, 0, 0),
                                        (vs.VS_IMPL_MFMA, vs.VS_SCHED_PIPELINED, 2, 4), (vs.VS_IMPL_MFMA, vs.VS_SCHED_RESIDENT, 0, 0),
-                                       (vs.VS_IMPL_MFMA, vs.VS_SCHED_RESIDENT, 40, 8), (vs.VS_IMPL_GENERIC, 0, 0, 0)):
+                                       (vs.VS_IMPL_MFMA, vs.VS_SCHED_RESIDENT, 40, 8), (vs.VS_IMPL_MFMA, vs.VS_SCHED_BALANCED, 5, 0),
+                                       (vs.VS_IMPL_MFMA, vs.VS_SCHED_BALANCED, 0, 8), (vs.VS_IMPL_GENERIC, 0, 0, 0)):
         got, status = _run(gu, inp, Hq, Hkv, d, nq, impl=impl, schedule=sched, num_splits=splits, waves=waves)
         assert (status == 0).all()
         _bounds(gu, got, ref, lens, f"impl {impl} schedule {sched} splits {splits} waves {waves}")
