@@ -163,7 +163,7 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     // the CUs at all and a share would be 32 steps of 64 keys if every sequence had that length
     // (reading the lengths and cutting the shares costs each kernel a dependent load and a few
     // microseconds: paged batches of 16 Qwen-7B-shaped sequences, equal splits against balanced shares,
-    // lengths drawn from 1024 .. 8192: 138 / 120, 135 / 109, 138 / 106, 127 / 99 us; all 4600: 93 / 100;
+    // lengths drawn from 1024 .. 8192: 138 / 118, 135 / 107, 138 / 106, 127 / 96 us; all 4600: 93 / 98;
     // all 8000: 150 / 156; drawn from 256 .. 2048: 50 / 57).
     const int bal_waves = waves ? waves : (nrb > 4 ? 8 : 4);
     const int bal_rg = (nrb + bal_waves - 1) / bal_waves;

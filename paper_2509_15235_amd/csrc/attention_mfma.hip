@@ -485,6 +485,9 @@ constexpr int kCombineBatch = 16; // splits whose partials are in flight togethe
 template <int D, bool BAL>
 __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p) {
     constexpr int DB = D / 32;
+    // partials in flight together. A sequence of the balanced schedule has a handful of pieces: a small
+    // batch keeps the kernel at eight waves per SIMD, which its thousands of one-wave workgroups need.
+    constexpr int BATCH = BAL ? 4 : kCombineBatch;
     __shared__ __attribute__((aligned(16))) uint16_t so[kRowBlock][32 + 8];
     __shared__ int32_t sslot[BAL ? kBalMaxChunks : 1]; // balanced schedule: the slots of this sequence's pieces
     // Workgroup id -> (unit, row group, row block of the group, channel block), in contiguous ranges
@@ -539,14 +542,14 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
         nload = nsplit;
     }
     auto slot_of = [&](int u) __attribute__((always_inline)) { return BAL ? sslot[u] : u; };
-    for (int s0 = 0; s0 < nload; s0 += kCombineBatch) {
-        f32x2 ml[kCombineBatch];
-        u32x4 o[kCombineBatch][2];
+    for (int s0 = 0; s0 < nload; s0 += BATCH) {
+        f32x2 ml[BATCH];
+        u32x4 o[BATCH][2];
 #pragma unroll
-        for (int u = 0; u < kCombineBatch; ++u)
+        for (int u = 0; u < BATCH; ++u)
             if (s0 + u < nload) ml[u] = __builtin_nontemporal_load(gml + slot_of(s0 + u) * kRowBlock);
 #pragma unroll
-        for (int u = 0; u < kCombineBatch; ++u)
+        for (int u = 0; u < BATCH; ++u)
             if (s0 + u < nload) {
                 const uint16_t* po = po0 + slot_of(s0 + u) * blk_stride * (kRowBlock * D);
 #pragma unroll
@@ -559,7 +562,7 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
         // this batch's maximum joins the running one; what was summed so far is rescaled
         float Mb = M;
 #pragma unroll
-        for (int u = 0; u < kCombineBatch; ++u)
+        for (int u = 0; u < BATCH; ++u)
             if (s0 + u < nsplit) Mb = fmaxf(Mb, ml[u][0]);
         const float resc = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mb); // nothing summed yet: 0
         den *= resc;
@@ -567,7 +570,7 @@ __global__ __launch_bounds__(kWave) void attn_combine_kernel(const AttnParams p)
         for (int q4 = 0; q4 < 4; ++q4) num[q4] *= resc;
         M = Mb;
 #pragma unroll
-        for (int u = 0; u < kCombineBatch; ++u)
+        for (int u = 0; u < BATCH; ++u)
             if (s0 + u < nsplit) { // uniform
                 // a split that saw no visible key for the row has max -inf, sum 0 and zero partials
                 // the split's row is stored normalised: its weight is 2^(m_s - M) * l_s
