@@ -40,6 +40,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the attention legs of the other configurations (C2 / C4 folded, C5 ragged batch)")
+    ap.add_argument("--only-leg", default="", choices=["", "C2", "C4", "C5"],
+                    help="run nothing but this configuration's attention leg and print its block (for profiler runs)")
+    ap.add_argument("--leg-schedule", type=int, default=0, help="vs_attn_schedule of --only-leg (0: the planner's choice)")
+    ap.add_argument("--leg-splits", type=int, default=0, help="num_splits of --only-leg")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--folded-splits", type=int, default=0)
     ap.add_argument("--seed", type=int, default=2024)
@@ -170,6 +174,17 @@ def main():
     vs.lib()  # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.only_leg:
+        def check_rc(rc):
+            if rc != 0:
+                raise RuntimeError(f"libvispec_verify: {vs.vs_strerror(rc)} ({rc})")
+        gleg = torch.Generator(device=dev)
+        gleg.manual_seed(args.seed)
+        blk = other_config_leg(vs, gen, torch, dev, torch.cuda.Stream(device=dev), gleg, args.only_leg, args.seed, check_rc,
+                               num_splits=args.leg_splits, schedule=args.leg_schedule)
+        print(json.dumps({"leg": args.only_leg, **blk}))
+        return
 
     cfg = gen.CONFIGS[args.config]
     L, T, Hq, Hkv, d, V = cfg.layers, cfg.T, cfg.Hq, cfg.Hkv, cfg.d, cfg.V

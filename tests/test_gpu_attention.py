@@ -82,7 +82,8 @@ def test_full_size_single_sequence(gu, oracle_mod, name):
 def test_c5_ragged_paged_batch(gu, oracle_mod):
     inp = gen.attention_inputs(gen.CONFIGS["C5"], 25)
     ref = oracle_mod.tree_attention(inp, threads=8)
-    _run_and_check(gu, oracle_mod, inp, ref=ref)
+    _, _, da = _run_and_check(gu, oracle_mod, inp, ref=ref)            # launch shape of the bench: balanced shares
+    assert da.plan().schedule == vs.VS_SCHED_BALANCED and da.plan().workgroups == 256
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=4)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=3, rows_per_wave=2, waves_per_group=8)
     _run_and_check(gu, oracle_mod, inp, ref=ref, num_splits=2, rows_per_wave=1, waves_per_group=4)
