@@ -168,8 +168,18 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     const int bal_waves = waves ? waves : (nrb > 4 ? 8 : 4);
     const int bal_rg = (nrb + bal_waves - 1) / bal_waves;
     const int bal_w_auto = kNumCUs / (d->Hkv * bal_rg) > kBalMaxChunks ? kBalMaxChunks : kNumCUs / (d->Hkv * bal_rg);
-    const bool balanced_ok = many && pipe_ok && splits <= 0 && d->B >= 2 && d->B <= kBalMaxSeqs && units0 * bal_rg < 200 &&
-                             bal_w_auto >= 2 && (int64_t)d->B * tiles >= 32 * (int64_t)bal_w_auto;
+    // Launches of more workgroups than CUs gain as well: shares replace a second, partly filled round
+    // of workgroups of unequal length (same heads; 32 sequences of 1024 .. 8192 keys: 242 -> 192 us; 40:
+    // 279 -> 226, all 3000 keys 202 -> 162; 64: 418 -> 340, all 3000 keys 227 -> 237). One full round of
+    // whole sequences (200 .. 256 workgroups) is left alone: unequal lengths would gain there too, equal
+    // ones lose the second kernel and the wait for the lengths (7 us of 60), and the host cannot tell
+    // which it has - such callers ask for VS_SCHED_BALANCED themselves.
+    const int bal_wgs = units0 * bal_rg;
+    // Eight-wave workgroups only: with four waves the unsplit plan keeps two workgroups on a CU where the
+    // shares would leave one (32 folded MHA layers of 3136 keys, HBM-bound: 308 us unsplit, 334 balanced).
+    const bool balanced_ok = many && pipe_ok && splits <= 0 && d->B >= 2 && d->B <= kBalMaxSeqs && bal_waves == 8 &&
+                             (bal_wgs < 200 || bal_wgs > kNumCUs) && bal_w_auto >= 2 &&
+                             (int64_t)d->B * tiles >= 32 * (int64_t)bal_w_auto;
     pl.schedule = d->schedule != VS_SCHED_AUTO ? d->schedule
                   : balanced_ok                ? VS_SCHED_BALANCED
                   : many && pipe_ok            ? VS_SCHED_PIPELINED
