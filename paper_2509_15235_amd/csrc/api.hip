@@ -159,27 +159,30 @@ Plan make_plan(const vs_attn_desc* d, int tree = 1) {
     // 6: 34.0 / 29.7, 8: 39.9 / 31.4, 11: 50.9 / 39.9, one C2 (MHA) layer 25.4 / 23.3; below
     // that the loop wins (one C3 sequence 19.1 / 22.5, two 21.7 / 23.3).
     // Balanced shares instead of equal splits per sequence: for batches whose sequences may differ in
-    // length (the host only knows the longest allowed one), when the launch needs key splits to fill
-    // the CUs at all and a share would be 32 steps of 64 keys if every sequence had that length
-    // (reading the lengths and cutting the shares costs each kernel a dependent load and a few
-    // microseconds: paged batches of 16 Qwen-7B-shaped sequences, equal splits against balanced shares,
-    // lengths drawn from 1024 .. 8192: 138 / 118, 135 / 107, 138 / 106, 127 / 96 us; all 4600: 93 / 98;
-    // all 8000: 150 / 156; drawn from 256 .. 2048: 50 / 57).
+    // length (the host only knows the longest allowed one). As many workgroups as the CUs hold at once
+    // (one of eight waves, two of four). Taken when the launch would need key splits to fill those
+    // places anyway, or when whole sequences would make more than one round and less than two - shares
+    // then replace a second, partly filled round of workgroups of unequal length - and a share would
+    // be 32 steps of 64 keys if every sequence had the longest allowed length (reading the lengths and
+    // cutting the shares costs each kernel a dependent load and a few microseconds).
+    // Paged batches, one layer, planner's other choice / balanced shares, lengths drawn from 1024 .. 8192
+    // unless stated. Qwen-7B heads (28 / 4), 16 sequences: 138 / 118, 135 / 107, 138 / 106, 127 / 96 us; all
+    // 4600 keys: 93 / 98; all 8000: 150 / 156; 256 .. 2048 keys: 50 / 57; 32 sequences: 242 / 192;
+    // 40: 279 / 226, all 3000 keys 202 / 162; 64: 418 / 340, all 3000 keys 227 / 237. LLaVA-7B heads (32 / 32),
+    // 4 sequences: 120 / 77; 8: 237 / 168; 12: 262 / 201; 24: 422 / 361; 32: 518 / 487, and 32 folded layers
+    // of 3136 keys 308 / 334.
+    // A launch that is one full round of whole sequences is left alone: unequal lengths would gain
+    // there too, equal ones lose the second kernel and the wait for the lengths (7 us of 60), and the
+    // host cannot tell which it has - such callers ask for VS_SCHED_BALANCED themselves. Two rounds or
+    // more are left alone as well: the gain shrinks with every round and equal lengths lose 4 - 8 %.
     const int bal_waves = waves ? waves : (nrb > 4 ? 8 : 4);
     const int bal_rg = (nrb + bal_waves - 1) / bal_waves;
-    const int bal_w_auto = kNumCUs / (d->Hkv * bal_rg) > kBalMaxChunks ? kBalMaxChunks : kNumCUs / (d->Hkv * bal_rg);
-    // Launches of more workgroups than CUs gain as well: shares replace a second, partly filled round
-    // of workgroups of unequal length (same heads; 32 sequences of 1024 .. 8192 keys: 242 -> 192 us; 40:
-    // 279 -> 226, all 3000 keys 202 -> 162; 64: 418 -> 340, all 3000 keys 227 -> 237). One full round of
-    // whole sequences (200 .. 256 workgroups) is left alone: unequal lengths would gain there too, equal
-    // ones lose the second kernel and the wait for the lengths (7 us of 60), and the host cannot tell
-    // which it has - such callers ask for VS_SCHED_BALANCED themselves.
+    const int bal_places = kNumCUs * (bal_waves == 8 ? 1 : 2);
+    const int bal_w_auto = bal_places / (d->Hkv * bal_rg) > kBalMaxChunks ? kBalMaxChunks : bal_places / (d->Hkv * bal_rg);
     const int bal_wgs = units0 * bal_rg;
-    // Eight-wave workgroups only: with four waves the unsplit plan keeps two workgroups on a CU where the
-    // shares would leave one (32 folded MHA layers of 3136 keys, HBM-bound: 308 us unsplit, 334 balanced).
-    const bool balanced_ok = many && pipe_ok && splits <= 0 && d->B >= 2 && d->B <= kBalMaxSeqs && bal_waves == 8 &&
-                             (bal_wgs < 200 || bal_wgs > kNumCUs) && bal_w_auto >= 2 &&
-                             (int64_t)d->B * tiles >= 32 * (int64_t)bal_w_auto;
+    const bool balanced_ok = many && pipe_ok && splits <= 0 && d->B >= 2 && d->B <= kBalMaxSeqs &&
+                             (bal_wgs * 32 < bal_places * 25 || (bal_wgs > bal_places && bal_wgs < 2 * bal_places)) &&
+                             bal_w_auto >= 2 && (int64_t)d->B * tiles >= 32 * (int64_t)bal_w_auto;
     pl.schedule = d->schedule != VS_SCHED_AUTO ? d->schedule
                   : balanced_ok                ? VS_SCHED_BALANCED
                   : many && pipe_ok            ? VS_SCHED_PIPELINED

@@ -156,13 +156,19 @@ def test_plan_and_workspace_sizes():
     assert vs.vs_attention_plan(_desc(B=16, max_prefix_len=8192, capacity=8300, stride_seq=4 * 8300 * 128,
                                       stride_head=8300 * 128, num_splits=3))[1].schedule == vs.VS_SCHED_PIPELINED
     assert vs.vs_attention_plan(_desc(B=8, stride_seq=4 * 1800 * 128))[1].schedule == vs.VS_SCHED_PIPELINED
-    # more workgroups than CUs: shares instead of a second, partly filled round; one full round stays as it is
-    big64 = _desc(B=64, max_prefix_len=8192, capacity=8300, stride_seq=4 * 8300 * 128, stride_head=8300 * 128)
-    rc, p64 = vs.vs_attention_plan(big64)
-    assert p64.schedule == vs.VS_SCHED_BALANCED and p64.num_splits == 32 and p64.workgroups == 256
-    assert vs.vs_attention_workspace_bytes(big64) == 4 * 96 * 448 * (128 * 2 + 8) + 256
-    assert vs.vs_attention_plan(_desc(B=32, max_prefix_len=8192, capacity=8300, stride_seq=4 * 8300 * 128,
-                                      stride_head=8300 * 128))[1].schedule == vs.VS_SCHED_PIPELINED
+    # more than one round of whole sequences and less than two: shares instead of a second, partly filled round;
+    # one or two full rounds stay as they are
+    big40 = _desc(B=40, max_prefix_len=8192, capacity=8300, stride_seq=4 * 8300 * 128, stride_head=8300 * 128)
+    rc, p40 = vs.vs_attention_plan(big40)
+    assert p40.schedule == vs.VS_SCHED_BALANCED and p40.num_splits == 32 and p40.workgroups == 256
+    assert vs.vs_attention_workspace_bytes(big40) == 4 * 72 * 448 * (128 * 2 + 8) + 256
+    for B in (32, 64):
+        assert vs.vs_attention_plan(_desc(B=B, max_prefix_len=8192, capacity=8300, stride_seq=4 * 8300 * 128,
+                                          stride_head=8300 * 128))[1].schedule == vs.VS_SCHED_PIPELINED
+    # four-wave workgroups (MHA): two per CU, hence 512 places and 16 shares per KV head
+    rc, pm8 = vs.vs_attention_plan(_desc(B=8, Hq=32, Hkv=32, max_prefix_len=8192, capacity=8300, stride_seq=32 * 8300 * 128,
+                                         stride_head=8300 * 128))
+    assert pm8.schedule == vs.VS_SCHED_BALANCED and pm8.waves_per_group == 4 and pm8.num_splits == 16 and pm8.workgroups == 512
     # few row blocks per unit (MHA): four waves
     mha = _desc(B=32, Hq=32, Hkv=32, max_prefix_len=3136, capacity=3300, stride_seq=32 * 3300 * 128, stride_head=3300 * 128)
     rc, pm2 = vs.vs_attention_plan(mha)
