@@ -545,7 +545,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // neighbour tile present and only prefix keys; the general form checks and masks.
     auto iteration = [&](auto cfast_tag, auto lfast_tag, auto set_tag, int ta) __attribute__((always_inline)) {
         constexpr bool FAST = decltype(cfast_tag)::value;
-        constexpr int SET = decltype(set_tag)::value; // register set of the group stashed here
+        // set_tag: the register set of the copy group that this iteration stashes
         using masked_t = std::integral_constant<bool, !FAST>;
         const int tb = ta + 1;
         const int g = ta >> 1;

@@ -138,3 +138,21 @@ def test_bad_block_is_reported(gu, oracle_mod):
     assert list(da.status.cpu().numpy()) == [0, 4, 0]
     gu.check_close(got[0], ref[0], *TIGHT_LONG, what="sequence 0")
     gu.check_close(got[2], ref[2], *TIGHT_LONG, what="sequence 2")
+
+
+def test_random_batches_and_share_counts(gu, oracle_mod):
+    """Seeded random batch sizes, lengths (some a single token, some a few thousand) and share counts."""
+    g = gen.rng(511, 1)
+    worst = 0.0
+    for case in range(14):
+        B = int(g.integers(1, 25))
+        hi = int(g.choice([40, 300, 3000]))
+        lens = g.integers(1, hi + 1, size=B).astype(np.int32)
+        shares = int(g.choice([0, 1, 2, 3, 5, 8, 13, 21, 32, 47, 64]))
+        waves = int(g.choice([4, 8]))
+        d = int(g.choice([64, 128]))
+        inp = gen.attention_inputs(_cfg(B=B, T=6, Hq=4, Hkv=2, d=d, max_depth=3, paged=bool(case % 2)), 600 + case, prefix_len=lens)
+        ref = oracle_mod.tree_attention(inp, threads=8)
+        _, w, _ = _check(gu, oracle_mod, inp, ref, num_splits=shares, waves_per_group=waves)
+        worst = max(worst, w)
+    print(f"random batches: worst {worst:.3e}")
