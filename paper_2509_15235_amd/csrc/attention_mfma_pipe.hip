@@ -159,8 +159,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // first key of the split in this (sequence, KV head) slice; only used when not paged
     const char* kfast = (const char*)(kbase + head_base + (int64_t)k0 * stride_tok);
     const char* vfast = (const char*)(vbase + head_base + (int64_t)k0 * stride_tok);
-    // LFAST: contiguous cache and a full tile, so the address is a wave-uniform base plus a
-    // per-lane constant and nothing needs clamping.
+    // LFAST: a full tile, so the address is a wave-uniform base plus a per-lane constant and nothing
+    // needs clamping.
     // Paged caches: the block ids of the tiles to come sit one per lane in two registers (a window of
     // 128 consecutive table entries, fetched with two coalesced loads and moved along as the tiles
     // advance), so a tile copy gets its block id with v_readlane instead of a scalar load per copy -
@@ -191,7 +191,21 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     auto load_tile = [&](auto lfast_tag, auto is_v, int t, u32x4(&r)[BPW]) __attribute__((always_inline)) {
         constexpr bool LFAST = decltype(lfast_tag)::value;
         constexpr bool ISV = decltype(is_v)::value;
-        if constexpr (LFAST) {
+        if constexpr (LFAST && PAGED) {
+            // a full tile of a paged cache: the RPI rows of a copy block lie in one cache block, so the
+            // address is a wave-uniform base (block id from the window, KV head, first row inside the
+            // block - all scalar arithmetic) plus the same per-lane constant as for a contiguous cache
+#pragma unroll
+            for (int j = 0; j < BPW; ++j) {
+                const int i = wave * BPW + j; // uniform per wave
+                if (NW * BPW == BPS || i < BPS) {
+                    const int r0 = k0 + t * kTileKeys + RPI * i;
+                    const int64_t sbase = head_base + (int64_t)bt_lookup(r0 >> p.block_shift) * p.stride_block +
+                                          (int64_t)((r0 & (p.block_size - 1)) * stride_tok);
+                    r[j] = *(const u32x4*)((const char*)((ISV ? vbase : kbase) + sbase) + lane_off);
+                }
+            }
+        } else if constexpr (LFAST) {
 #pragma unroll
             for (int j = 0; j < BPW; ++j) {
                 const int i = wave * BPW + j; // uniform per wave
@@ -606,11 +620,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_pipe_kernel(const AttnPa
     // of the range last), so three loops in a row cover every case. Iteration ta loads
     // group ta/2 + 2 = tiles up to ta + 8.
     int ta = 0;
-    if constexpr (!PAGED)
-        for (; ta + 2 < fast_end && ta + 10 < n_full; ta += 4) {
-            iteration(T{}, T{}, S0{}, ta);
-            iteration(T{}, T{}, S1{}, ta + 2);
-        }
+    for (; ta + 2 < fast_end && ta + 10 < n_full; ta += 4) {
+        iteration(T{}, T{}, S0{}, ta);
+        iteration(T{}, T{}, S1{}, ta + 2);
+    }
     for (; ta + 2 < fast_end; ta += 4) {
         iteration(T{}, F{}, S0{}, ta);
         iteration(T{}, F{}, S1{}, ta + 2);
