@@ -108,17 +108,18 @@ def test_layers_folded_into_batch(gu, oracle_mod):
     _run_and_check(gu, oracle_mod, inp, ref=ref, schedule=vs.VS_SCHED_RESIDENT)
 
 
-@pytest.mark.parametrize("name,seqs", [("C3", None), ("C4", [0, 13, 27])])
-def test_folded_launch_at_full_size(gu, oracle_mod, name, seqs):
-    """bench.py's roofline launch exactly as it is timed: every layer of one step as a batch entry (28 x the
-    configuration's sequence), the planner's choice - pipelined, 224 workgroups, no key split. C3: every entry
-    against the oracle; C4 (6684-token prefixes): first, middle and last entry."""
+@pytest.mark.parametrize("name,seqs,wgs", [("C3", None, 224), ("C4", [0, 13, 27], 224), ("C2", [0, 31], 1024)])
+def test_folded_launch_at_full_size(gu, oracle_mod, name, seqs, wgs):
+    """bench.py's roofline launch exactly as it is timed: every layer of one step as a batch entry (28 or 32 x
+    the configuration's sequence), the planner's choice - pipelined, no key split, 224 workgroups of eight waves
+    (GQA) or 1024 of four (MHA). C3: every entry against the oracle; C4 (6684-token prefixes) and C2: sampled
+    entries."""
     base = gen.CONFIGS[name]
     cfg = dataclasses.replace(base, B=base.layers, prefix=[base.prefix[0]] * base.layers)
     inp = gen.attention_inputs(cfg, 40 + int(name[1]))
     da = gu.DeviceAttn(inp)
     pl = da.plan()
-    assert pl.schedule == vs.VS_SCHED_PIPELINED and pl.num_splits == 1 and pl.workgroups == 224 and pl.combine == 0
+    assert pl.schedule == vs.VS_SCHED_PIPELINED and pl.num_splits == 1 and pl.workgroups == wgs and pl.combine == 0
     got = da.run()
     assert (da.status.cpu().numpy() == 0).all()
     which = list(range(cfg.B)) if seqs is None else seqs
